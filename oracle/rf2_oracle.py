@@ -1,0 +1,279 @@
+"""CPU oracle for the RainFusion2.0 block-sparse attention layer (fp64, NumPy).
+
+THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only the test-suite, the smoke
+check and the benchmark's CPU-baseline leg may import it.  It shares no code,
+table or helper with the HIP library and never imports it.
+
+It is a plain, slow, step-by-step transcription of what one attention layer of
+the method computes, in the paper's order:
+
+  token permutation (Sec. 3.3, Sec. 3.4 last paragraph)
+  -> block representative tokens            (Sec. 3.2, eqs. 5, 6)
+  -> block scores                           (Sec. 3.2, eq. 7)
+  -> top-n block selection + first-frame sink (Sec. 3.2, eq. 8; Sec. 3.4)
+  -> block-sparse flash attention           (Sec. 3.1, eqs. 1-4 and the skip rule)
+  -> inverse permutation                    (implied by Sec. 3.3)
+
+All floating point work is float64 on the exact values of the bf16 inputs.
+Every function works on ONE (batch, head) slice: 2-D arrays [N, d].
+
+Pins (see tests/test_oracle_*.py): permutation vs. hand-written fixtures, a
+nested-loop window enumeration, bijection and special cases; budget arithmetic
+vs. a table of independently derived sizes; selection vs. a repeated-maximum
+brute force and hand-built ties; attention vs. a library dense/masked softmax
+attention in fp64, explicit per-query Python loops, and closed-form cases
+(V == 1, one-hot V).  Fidelity of the window order to the authors' unpublished
+permutation: parity unpinned (Sec. 3.3 defers its details).
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+BUDGET_GLOBAL = 0
+BUDGET_ROW_INCL_SINK = 1
+BUDGET_ROW_PLUS_SINK = 2
+
+
+# --------------------------------------------------------------------------
+# inputs
+# --------------------------------------------------------------------------
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact value of bf16 numbers given as their 16-bit patterns."""
+    u = np.asarray(bits).view(np.uint16).astype(np.uint32) << np.uint32(16)
+    return u.view(np.float32).astype(np.float64)
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.3 / Sec. 3.4: spatiotemporal window permutation, sink relocated
+# --------------------------------------------------------------------------
+def default_window(block: int, video: bool) -> tuple[int, int, int]:
+    """Window whose volume equals the block size, so one interior window is one
+    block (the paper gives no shape; this is a parameter of the method)."""
+    table = {(128, True): (2, 8, 8), (128, False): (1, 8, 16),
+             (64, True): (4, 4, 4), (64, False): (1, 8, 8)}
+    return table[(block, video)]
+
+
+def _window_order(frames: np.ndarray, H: int, W: int, wt: int, wh: int, ww: int) -> np.ndarray:
+    """Source indices of the tokens of `frames` (consecutive frame numbers)
+    listed window by window (windows in raster order over the window grid) and
+    in raster order inside each window.  Edge windows are simply smaller."""
+    t0 = int(frames[0])
+    t, h, w = np.meshgrid(frames, np.arange(H), np.arange(W), indexing="ij")
+    t, h, w = t.ravel(), h.ravel(), w.ravel()
+    tp = t - t0
+    # np.lexsort sorts by the LAST key first.
+    order = np.lexsort((w % ww, h % wh, tp % wt, w // ww, h // wh, tp // wt))
+    return ((t * H + h) * W + w)[order]
+
+
+def perm_table(T: int, H: int, W: int, wt: int, wh: int, ww: int,
+               sink_frames: int = 0, sink_at_end: bool = True) -> np.ndarray:
+    """perm[p] = raster index n=(t*H+h)*W+w of the token placed at permuted
+    position p.  Body frames (t >= sink_frames) use 3-D windows (wt,wh,ww);
+    sink frames use 2-D windows (1,wh,ww) frame by frame and are placed after
+    the body (Sec. 3.4, last paragraph) or before it (Fig. 1)."""
+    body = _window_order(np.arange(sink_frames, T), H, W, wt, wh, ww)
+    if sink_frames == 0:
+        return body.astype(np.int64)
+    sink = _window_order(np.arange(0, sink_frames), H, W, 1, wh, ww)
+    parts = (body, sink) if sink_at_end else (sink, body)
+    return np.concatenate(parts).astype(np.int64)
+
+
+def inverse_table(perm: np.ndarray) -> np.ndarray:
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(perm.size, dtype=perm.dtype)
+    return inv
+
+
+def permute(X: np.ndarray, perm: np.ndarray) -> np.ndarray:
+    """X_p[p] = X[perm[p]]."""
+    return X[perm]
+
+
+def unpermute(Xp: np.ndarray, perm: np.ndarray) -> np.ndarray:
+    """X[perm[p]] = X_p[p]."""
+    X = np.empty_like(Xp)
+    X[perm] = Xp
+    return X
+
+
+# --------------------------------------------------------------------------
+# blocks, sink block range, budget
+# --------------------------------------------------------------------------
+def n_blocks(N: int, b: int) -> int:
+    return -(-N // b)
+
+
+def block_slice(i: int, N: int, b: int) -> slice:
+    return slice(i * b, min((i + 1) * b, N))
+
+
+def sink_block_range(N: int, frame_tokens: int, b: int, sink_frames: int,
+                     sink_at_end: bool = True) -> tuple[int, int]:
+    """[begin, end) of the blocks that hold at least one sink-frame token."""
+    n_sink = sink_frames * frame_tokens
+    Tb = n_blocks(N, b)
+    if n_sink == 0:
+        return (0, 0)
+    if sink_at_end:
+        return ((N - n_sink) // b, Tb)
+    return (0, -(-n_sink // b))
+
+
+def budget(Tb: int, n_sink_blocks: int, sparsity: float, mode: int = BUDGET_GLOBAL) -> tuple[int, int]:
+    """(k_row, k_sel): blocks kept per non-sink row in total, and those chosen
+    by score among the non-sink columns.  `sparsity` is taken as a float32
+    value; the arithmetic is IEEE double.
+
+    GLOBAL: the target is the skipped fraction of the whole Tb x Tb mask, sink
+    rows and columns included.  ROW_INCL_SINK: each row keeps ceil((1-s)Tb)
+    blocks, the sink among them.  ROW_PLUS_SINK: each row selects ceil((1-s)Tb)
+    blocks on top of the sink."""
+    keep = 1.0 - float(np.float32(sparsity))
+    nS = n_sink_blocks
+    if nS >= Tb:
+        return (Tb, 0)
+    if mode == BUDGET_GLOBAL:
+        k_row = int(math.floor((keep * Tb * Tb - float(nS) * Tb) / float(Tb - nS)))
+    elif mode == BUDGET_ROW_INCL_SINK:
+        k_row = int(math.ceil(keep * Tb))
+    elif mode == BUDGET_ROW_PLUS_SINK:
+        k_row = int(math.ceil(keep * Tb)) + nS
+    else:
+        raise ValueError("budget mode")
+    k_row = min(max(k_row, nS, 1), Tb)
+    return (k_row, k_row - nS)
+
+
+def kept_pairs(Tb: int, n_sink_blocks: int, k_row: int) -> int:
+    return (Tb - n_sink_blocks) * k_row + n_sink_blocks * Tb
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.2: representative tokens, block scores, top-n selection; Sec. 3.4 sink
+# --------------------------------------------------------------------------
+def pool_blocks(Xp: np.ndarray, b: int) -> np.ndarray:
+    """Eqs. (5), (6): mean over the rows of each block (a ragged last block is
+    averaged over the rows it really has)."""
+    N = Xp.shape[0]
+    return np.stack([Xp[block_slice(i, N, b)].mean(axis=0) for i in range(n_blocks(N, b))])
+
+
+def block_scores(qbar: np.ndarray, kbar: np.ndarray) -> np.ndarray:
+    """Eq. (7): S_hat[i, j] = <qbar_i, kbar_j>, no scaling."""
+    return qbar @ kbar.T
+
+
+def select_blocks(S_hat: np.ndarray, k_sel: int, sink_begin: int, sink_end: int) -> np.ndarray:
+    """Eq. (8) with the sink of Sec. 3.4.  Non-sink row i keeps the k_sel
+    non-sink columns with the largest S_hat[i, :] (equal scores: lower column
+    first) and every sink column; sink rows keep every column."""
+    Tb = S_hat.shape[0]
+    M = np.zeros((Tb, Tb), dtype=bool)
+    cand = np.array([j for j in range(Tb) if not (sink_begin <= j < sink_end)], dtype=np.int64)
+    for i in range(Tb):
+        if sink_begin <= i < sink_end:
+            M[i, :] = True
+            continue
+        s = S_hat[i, cand]
+        order = np.lexsort((cand, -s))          # by -score, then by column
+        M[i, cand[order[:k_sel]]] = True
+        M[i, sink_begin:sink_end] = True
+    return M
+
+
+def selection_gap(S_hat: np.ndarray, k_sel: int, sink_begin: int, sink_end: int) -> np.ndarray:
+    """Per row: (k_sel-th largest candidate score) - ((k_sel+1)-th largest);
+    +inf where the row has no boundary (sink row, or every candidate kept)."""
+    Tb = S_hat.shape[0]
+    cand = np.array([j for j in range(Tb) if not (sink_begin <= j < sink_end)], dtype=np.int64)
+    gap = np.full(Tb, np.inf)
+    if k_sel <= 0 or k_sel >= cand.size:
+        return gap
+    for i in range(Tb):
+        if sink_begin <= i < sink_end:
+            continue
+        s = np.sort(S_hat[i, cand])[::-1]
+        gap[i] = s[k_sel - 1] - s[k_sel]
+    return gap
+
+
+def mask_to_lists(M: np.ndarray) -> list[np.ndarray]:
+    """Ascending kept-column list of every row."""
+    return [np.flatnonzero(M[i]).astype(np.int32) for i in range(M.shape[0])]
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.1: block-sparse flash attention, eqs. (1)-(4) + skip rule
+# --------------------------------------------------------------------------
+def block_sparse_attention(Qp: np.ndarray, Kp: np.ndarray, Vp: np.ndarray, M: np.ndarray,
+                           b: int, q_blocks=None, return_lse: bool = False):
+    """Output rows of the requested Q blocks (default: all), by the online
+    recurrences: for each kept block j in ascending order
+        S = Q_i K_j^T / sqrt(d)                                   (1)
+        m_new = max(m, rowmax S),  P = exp(S - m_new)             (2)
+        l = exp(m - m_new) l + rowsum P                           (3)
+        O = diag(exp(m - m_new)) O + P V_j                        (4)
+    and finally O_i = diag(l)^-1 O.  Blocks with M[i, j] == 0 are skipped."""
+    N, d = Qp.shape
+    Tb = n_blocks(N, b)
+    rows = range(Tb) if q_blocks is None else q_blocks
+    dv = Vp.shape[1]
+    O = np.zeros((N, dv))
+    lse = np.full(N, np.nan)
+    inv_sqrt_d = 1.0 / math.sqrt(d)
+    for i in rows:
+        qs = block_slice(i, N, b)
+        Qi = Qp[qs]
+        m = np.full((Qi.shape[0], 1), -np.inf)
+        l = np.zeros((Qi.shape[0], 1))
+        acc = np.zeros((Qi.shape[0], dv))
+        for j in range(Tb):
+            if not M[i, j]:
+                continue
+            ks = block_slice(j, N, b)
+            S = (Qi @ Kp[ks].T) * inv_sqrt_d
+            m_new = np.maximum(m, S.max(axis=1, keepdims=True))
+            P = np.exp(S - m_new)
+            scale = np.exp(m - m_new)
+            l = scale * l + P.sum(axis=1, keepdims=True)
+            acc = scale * acc + P @ Vp[ks]
+            m = m_new
+        O[qs] = acc / l
+        lse[qs] = (m + np.log(l))[:, 0]
+    if q_blocks is not None:
+        keep = np.zeros(N, dtype=bool)
+        for i in q_blocks:
+            keep[block_slice(i, N, b)] = True
+        O[~keep] = np.nan
+    return (O, lse) if return_lse else O
+
+
+# --------------------------------------------------------------------------
+# whole layer for one head
+# --------------------------------------------------------------------------
+def layer(Q: np.ndarray, K: np.ndarray, V: np.ndarray, *, T: int, H: int, W: int, block: int,
+          sparsity: float, sink_frames: int = 0, sink_at_end: bool = True,
+          window=None, budget_mode: int = BUDGET_GLOBAL, q_blocks=None) -> dict:
+    """All stages for one (batch, head).  Q, K, V: [N, d] float64 in [T,H,W]
+    raster order.  Returns every intermediate."""
+    N = T * H * W
+    assert Q.shape[0] == N
+    wt, wh, ww = window if window is not None else default_window(block, T > 1)
+    perm = perm_table(T, H, W, wt, wh, ww, sink_frames, sink_at_end)
+    Qp, Kp, Vp = permute(Q, perm), permute(K, perm), permute(V, perm)
+    qbar, kbar = pool_blocks(Qp, block), pool_blocks(Kp, block)
+    S_hat = block_scores(qbar, kbar)
+    Tb = n_blocks(N, block)
+    sb, se = sink_block_range(N, H * W, block, sink_frames, sink_at_end)
+    k_row, k_sel = budget(Tb, se - sb, sparsity, budget_mode)
+    M = select_blocks(S_hat, k_sel, sb, se)
+    Op, lse = block_sparse_attention(Qp, Kp, Vp, M, block, q_blocks=q_blocks, return_lse=True)
+    O = unpermute(Op, perm)
+    return dict(perm=perm, Qp=Qp, Kp=Kp, Vp=Vp, qbar=qbar, kbar=kbar, S_hat=S_hat, M=M,
+                sink=(sb, se), k_row=k_row, k_sel=k_sel, Op=Op, lse=lse, O=O,
+                gap=selection_gap(S_hat, k_sel, sb, se))

@@ -1,0 +1,111 @@
+"""Pins for the oracle's pooling, scoring and block selection (CPU only)."""
+import numpy as np
+import pytest
+
+from oracle import rf2_oracle as orc
+
+
+def test_pool_constant_block_and_weighted_sum():
+    rng = np.random.default_rng(1)
+    N, d, b = 300, 8, 64                       # last block has 44 rows
+    X = rng.standard_normal((N, d))
+    X[64:128] = X[64]                          # a block of identical rows
+    m = orc.pool_blocks(X, b)
+    assert m.shape == (5, d)
+    assert np.abs(m[1] - X[64]).max() < 1e-14
+    cnt = np.array([64, 64, 64, 64, 44])[:, None]
+    assert np.allclose((m * cnt).sum(0), X.sum(0), rtol=0, atol=1e-11)
+    assert np.allclose(m[4], X[256:].sum(0) / 44, rtol=0, atol=1e-14)   # ragged block: own count
+
+
+def test_scores_definition_by_loops():
+    rng = np.random.default_rng(2)
+    q, k = rng.standard_normal((5, 7)), rng.standard_normal((6, 7))
+    S = orc.block_scores(q, k)
+    for i in range(5):
+        for j in range(6):
+            assert abs(S[i, j] - sum(q[i, c] * k[j, c] for c in range(7))) < 1e-13
+    assert np.allclose(orc.block_scores(q, q), orc.block_scores(q, q).T)
+
+
+def brute_force_select(S, k_sel, sb, se):
+    """Repeatedly take the maximum (first occurrence) among remaining non-sink columns."""
+    Tb = S.shape[0]
+    M = np.zeros((Tb, Tb), dtype=bool)
+    for i in range(Tb):
+        if sb <= i < se:
+            M[i] = True
+            continue
+        left = [j for j in range(Tb) if not (sb <= j < se)]
+        for _ in range(k_sel):
+            best = left[0]
+            for j in left:
+                if S[i, j] > S[i, best]:
+                    best = j
+            M[i, best] = True
+            left.remove(best)
+        M[i, sb:se] = True
+    return M
+
+
+@pytest.mark.parametrize("Tb,sb,se,k_sel", [(12, 9, 12, 3), (12, 0, 0, 5), (12, 0, 2, 4), (7, 5, 7, 0), (9, 0, 0, 9)])
+def test_select_vs_brute_force(Tb, sb, se, k_sel):
+    rng = np.random.default_rng(Tb * 100 + k_sel)
+    S = rng.standard_normal((Tb, Tb))
+    S[1, :] = np.round(S[1, :])                # many exact ties in one row
+    M = orc.select_blocks(S, k_sel, sb, se)
+    assert np.array_equal(M, brute_force_select(S, k_sel, sb, se))
+    for i in range(Tb):
+        if sb <= i < se:
+            assert M[i].all()
+        else:
+            assert M[i].sum() == k_sel + (se - sb) and M[i, sb:se].all()
+            cand = np.array([j for j in range(Tb) if not (sb <= j < se)])
+            kept, dropped = S[i, cand][M[i, cand]], S[i, cand][~M[i, cand]]
+            if kept.size and dropped.size:
+                assert kept.min() >= dropped.max()
+
+
+def test_ties_prefer_lower_column():
+    S = np.array([[1.0, 3.0, 3.0, 3.0, 0.0],
+                  [2.0, 2.0, 2.0, 2.0, 2.0]])
+    S = np.vstack([S, np.zeros((3, 5))])
+    M = orc.select_blocks(S, 2, 0, 0)
+    assert M[0].tolist() == [False, True, True, False, False]
+    assert M[1].tolist() == [True, True, False, False, False]
+
+
+def test_sparsity_zero_keeps_all_and_invariances():
+    rng = np.random.default_rng(3)
+    N, d, b = 640, 16, 64
+    Q, K = rng.standard_normal((N, d)), rng.standard_normal((N, d))
+    Tb = orc.n_blocks(N, b)
+    k_row, k_sel = orc.budget(Tb, 2, 0.0)
+    S = orc.block_scores(orc.pool_blocks(Q, b), orc.pool_blocks(K, b))
+    assert orc.select_blocks(S, k_sel, 8, 10).all()
+    k_row, k_sel = orc.budget(Tb, 2, 0.5)
+    M = orc.select_blocks(S, k_sel, 8, 10)
+    # shuffling tokens inside blocks, or scaling Q by a positive constant, cannot change the mask
+    Q2, K2 = Q.copy(), K.copy()
+    for i in range(Tb):
+        Q2[i * b:(i + 1) * b] = Q[i * b:(i + 1) * b][rng.permutation(b)]
+        K2[i * b:(i + 1) * b] = K[i * b:(i + 1) * b][rng.permutation(b)]
+    S2 = orc.block_scores(orc.pool_blocks(Q2, b), orc.pool_blocks(K2, b))
+    assert np.array_equal(orc.select_blocks(S2, k_sel, 8, 10), M)
+    assert np.array_equal(orc.select_blocks(4.0 * S, k_sel, 8, 10), M)
+
+
+def test_selection_gap():
+    S = np.array([[5.0, 1.0, 4.0, 3.999, 9.0],
+                  [1.0, 2.0, 3.0, 4.0, 9.0],
+                  [0.0, 0.0, 0.0, 0.0, 0.0],
+                  [0.0, 0.0, 0.0, 0.0, 0.0],
+                  [7.0, 7.0, 7.0, 7.0, 7.0]])
+    gap = orc.selection_gap(S, 2, 4, 5)        # column/row 4 is the sink
+    assert abs(gap[0] - 0.001) < 1e-12 and gap[1] == 1.0 and gap[2] == 0.0 and np.isinf(gap[4])
+    assert np.isinf(orc.selection_gap(S, 4, 4, 5)).all()       # every candidate kept: no boundary
+
+
+def test_mask_to_lists():
+    M = np.array([[1, 0, 1], [0, 0, 1], [1, 1, 1]], dtype=bool)
+    assert [l.tolist() for l in orc.mask_to_lists(M)] == [[0, 2], [2], [0, 1, 2]]
