@@ -1,0 +1,166 @@
+/*
+ * rf2.h -- C ABI of librf2: one block-sparse attention layer of a Diffusion
+ * Transformer as described by RainFusion2.0 (arXiv 2512.24086), for one AMD
+ * MI355X (gfx950).
+ *
+ * The layer, in the order the paper gives it (Fig. 1):
+ *   rf2_permute           Sec. 3.3 window permutation (+ Sec. 3.4 first frame moved
+ *                         to the sequence end) fused with the block means of
+ *                         Sec. 3.2, eqs. (5) and (6)
+ *   rf2_predict_mask      Sec. 3.2, eq. (7) block scores and eq. (8) top-n
+ *                         selection, plus the first-frame sink of Sec. 3.4
+ *   rf2_block_sparse_attn Sec. 3.1, eqs. (1)-(4) with the block skip rule
+ *   rf2_unpermute         inverse of the Sec. 3.3 permutation
+ *
+ * Conventions
+ *   - Every function returns an int: RF2_OK (0) or a negative RF2_ERR_* code.
+ *     Nothing throws, aborts or synchronises the device behind the caller's back.
+ *   - Pointers named *_host are host memory; every other tensor pointer is DEVICE
+ *     memory on the device that was current when the plan was created.  The
+ *     caller owns all tensors; the plan owns only its index tables.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued asynchronously on it.
+ *   - Tensors are dense, contiguous, row-major in the stated shape.  "bf16" is the
+ *     16-bit brain float (upper half of an IEEE binary32).
+ *   - Arguments are validated on the host before any launch; a failed call has
+ *     launched nothing.
+ *   - A plan is immutable after creation; calls sharing a plan may run
+ *     concurrently on different streams.
+ *
+ * Notation: B batch, Hh heads, d head_dim, N = T*H*W tokens, b block size
+ * (b_q = b_k = b), Tb = ceil(N/b) blocks, N_pad = Tb*b.
+ */
+#ifndef RF2_H
+#define RF2_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  RF2_OK = 0,
+  RF2_ERR_INVALID_ARG = -1, /* NULL where not allowed, size out of range, inconsistent config */
+  RF2_ERR_UNSUPPORTED = -2, /* head_dim or block size this build has no kernel for */
+  RF2_ERR_ALLOC = -3,       /* host or device allocation of the plan's tables failed */
+  RF2_ERR_HIP = -4          /* a HIP runtime call or kernel launch reported an error */
+};
+
+/* How `sparsity` becomes a per-row block count (the paper only names a sparsity level). */
+enum {
+  RF2_BUDGET_GLOBAL = 0,        /* s = skipped fraction of the whole Tb x Tb block mask, sink included */
+  RF2_BUDGET_ROW_INCL_SINK = 1, /* each row keeps ceil((1-s) Tb) blocks, sink blocks among them */
+  RF2_BUDGET_ROW_PLUS_SINK = 2  /* each row selects ceil((1-s) Tb) blocks in addition to the sink */
+};
+
+typedef struct {
+  int32_t batch, heads, head_dim; /* head_dim in {64, 128} */
+  int32_t T, H, W;                /* latent grid (frames, height, width); T = 1 for an image */
+  int32_t wt, wh, ww;             /* window of the Sec. 3.3 permutation; all three 0 = default:
+                                     b=128: video (2,8,8), image (1,8,16); b=64: video (4,4,4), image (1,8,8) */
+  int32_t block;                  /* b in {64, 128} */
+  int32_t sink_frames;            /* leading frames treated as the Sec. 3.4 sink: 0 or more, < T */
+  int32_t sink_at_end;            /* 1: sink tokens placed after the body (Sec. 3.4, last paragraph); 0: before */
+  float sparsity;                 /* target s in [0, 1) */
+  int32_t budget_mode;            /* RF2_BUDGET_* */
+} rf2_config;
+
+typedef struct {
+  int64_t N, N_pad;
+  int32_t n_blocks;         /* Tb */
+  int32_t last_block_valid; /* tokens in the last block, 1..b */
+  int32_t sink_block_begin, sink_block_end; /* [begin, end) of blocks holding >= 1 sink token; equal if none */
+  int32_t k_row;            /* blocks kept by every non-sink row, sink blocks included */
+  int32_t k_sel;            /* of those, chosen by score among non-sink columns = k_row - (end - begin) */
+  int32_t wt, wh, ww;       /* window actually used */
+  int64_t kept_pairs_per_head;
+  double achieved_sparsity; /* 1 - kept_pairs_per_head / Tb^2 */
+  int64_t workspace_bytes;  /* size rf2_predict_mask needs at `workspace` (currently 0) */
+} rf2_info;
+
+typedef struct rf2_plan rf2_plan; /* opaque */
+
+/*
+ * Host-only set-up (Sec. 3.3, 3.4): validates `cfg`, builds the permutation table
+ *   perm[p] = raster index (t*H + h)*W + w of the token at permuted position p
+ * and uploads it to the current device.  Window order: body frames (t >= sink_frames)
+ * are cut into windows of (wt, wh, ww) tokens, edge windows truncated; windows are
+ * listed in raster order of the window grid, tokens in raster order inside a window;
+ * sink frames use (1, wh, ww) windows frame by frame and follow (sink_at_end) or
+ * precede the body.  *out receives a plan to be released with rf2_plan_destroy.
+ * If the process sees no HIP device the plan is host-only: rf2_plan_info and
+ * rf2_plan_perm work, every compute call returns RF2_ERR_HIP.
+ * Limits: N <= 2^24, Tb <= 2048, B*Hh <= 65535 (RF2_ERR_UNSUPPORTED beyond).
+ */
+int rf2_plan_create(const rf2_config* cfg, rf2_plan** out);
+int rf2_plan_destroy(rf2_plan* plan);
+int rf2_plan_info(const rf2_plan* plan, rf2_info* out);
+/* Copies the tables to host arrays of N int32 each (either may be NULL): inv[perm[p]] = p. */
+int rf2_plan_perm(const rf2_plan* plan, int32_t* perm_host, int32_t* inv_host);
+
+/*
+ * Sec. 3.3 permutation of Q, K, V fused with the block means of eqs. (5), (6).
+ *   q, k, v : [B, Hh, N, d] bf16, tokens in [T, H, W] raster order        (in)
+ *   qp, kp  : [B, Hh, N_pad, d] bf16, qp[p] = q[perm[p]]; rows >= N zero  (out)
+ *   vp      : [B, Hh, Tb, d, b] bf16, "key-major tiles": element (blk, c, s) holds
+ *             channel c of the permuted value row  blk*b + 16*(s/16) + rho(s%16),
+ *             rho(r) = r for r in 0..3 and 12..15, r+4 for 4..7, r-4 for 8..11
+ *             (each 16-key group stores keys 0-3, 8-11, 4-7, 12-15); rows >= N zero.
+ *             This is the operand layout the attention kernel's P.V product
+ *             consumes straight from memory.                               (out)
+ *   qbar, kbar : [B, Hh, Tb, d] fp32 means over the valid rows of each block of
+ *             qp / kp (the last block divides by last_block_valid).  Pass both
+ *             NULL to skip pooling.                                        (out)
+ * v/vp or q/qp/k/kp groups may not be NULL individually: all six are required.
+ */
+int rf2_permute(const rf2_plan* plan, const void* q, const void* k, const void* v,
+                void* qp, void* kp, void* vp, float* qbar, float* kbar, void* stream);
+
+/*
+ * Eq. (7): S_hat[i][j] = <qbar_i, kbar_j> in fp32; eq. (8): every non-sink row i keeps
+ * the k_sel non-sink columns with the largest S_hat[i][.] (equal scores: lower column
+ * first) and all sink columns; sink rows keep every column (Sec. 3.4).
+ *   blk_idx : [B, Hh, Tb, k_row] int32, kept columns of each row in ascending order;
+ *             for sink rows the first k_row entries of the row are 0..k_row-1 and the
+ *             row is flagged dense by its count                            (out)
+ *   blk_cnt : [B, Hh, Tb] int32: k_row, or Tb for a row that keeps everything (out)
+ *   mask_dense : optional [B, Hh, Tb, Tb] uint8 0/1, may be NULL            (out)
+ *   scores  : optional [B, Hh, Tb, Tb] fp32 S_hat, may be NULL              (out)
+ *   workspace : rf2_info.workspace_bytes of device memory (may be NULL when 0)
+ */
+int rf2_predict_mask(const rf2_plan* plan, const float* qbar, const float* kbar,
+                     int32_t* blk_idx, int32_t* blk_cnt, uint8_t* mask_dense, float* scores,
+                     void* workspace, void* stream);
+
+/*
+ * Sec. 3.1: for every Q block i, softmax(Q_i K_j^T / sqrt(d)) V_j accumulated over
+ * the kept blocks j by the online recurrences (1)-(4); blocks not listed are skipped.
+ * Keys at permuted positions >= N are excluded.  bf16 operands, fp32 accumulation.
+ *   qp, kp, vp : as written by rf2_permute                                 (in)
+ *   blk_idx, blk_cnt : any valid list in the rf2_predict_mask format: row stride
+ *             k_row, entries ascending, distinct, in [0, Tb), count in [1, k_row]
+ *             or == Tb (then the list is ignored and all blocks are used).
+ *             Entries are NOT checked on the device: an index outside [0, Tb)
+ *             is undefined behaviour.                                      (in)
+ *   op      : [B, Hh, N_pad, d] bf16 in permuted order; rows >= N unspecified (out)
+ *   lse     : optional [B, Hh, N_pad] fp32 natural-log sum-exp of the scaled
+ *             logits over the kept keys, may be NULL                       (out)
+ */
+int rf2_block_sparse_attn(const rf2_plan* plan, const void* qp, const void* kp, const void* vp,
+                          const int32_t* blk_idx, const int32_t* blk_cnt, void* op, float* lse,
+                          void* stream);
+
+/* o[perm[p]] = op[p] for p < N.  op: [B, Hh, N_pad, d] bf16; o: [B, Hh, N, d] bf16. */
+int rf2_unpermute(const rf2_plan* plan, const void* op, void* o, void* stream);
+
+/* Static description of an error code; for RF2_ERR_HIP the text of the last HIP error seen
+ * by the calling thread is appended. */
+const char* rf2_strerror(int code);
+/* major*10000 + minor*100 + patch */
+int rf2_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RF2_H */

@@ -1,0 +1,31 @@
+// Internal declarations shared by the translation units of librf2 (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "rf2.h"
+
+struct rf2_plan {
+  rf2_config cfg;
+  rf2_info info;
+  int device;
+  std::vector<int32_t> perm, inv;  // host copies, N entries each
+  int32_t* d_perm;                 // device, N_pad entries; -1 marks a padding row
+  int32_t* d_inv;                  // device, N entries
+  int32_t* d_row_order;            // device, 8*rows_per_xcd entries: Q block handled by each workgroup slot, -1 = none
+  int32_t rows_per_xcd;
+};
+
+// Remembers the text of a failed HIP call for rf2_strerror (per calling thread).
+int rf2_note_hip_error(hipError_t e);
+
+#define RF2_HIP(call)                                   \
+  do {                                                  \
+    hipError_t e__ = (call);                            \
+    if (e__ != hipSuccess) return rf2_note_hip_error(e__); \
+  } while (0)
+
+// Launch check used after every kernel launch.
+#define RF2_LAUNCH_CHECK() RF2_HIP(hipGetLastError())

@@ -1,0 +1,157 @@
+// Block-mask prediction: S_hat = qbar kbar^T (Sec. 3.2, eq. 7) in fp32 on the matrix cores,
+// then per-row top-n selection (eq. 8) with the first-frame sink (Sec. 3.4), fused in one
+// kernel.  A workgroup owns 16 rows of one head: its 4 wavefronts first fill a 16 x Tb
+// score strip in LDS, then each wavefront selects 4 of the rows with a bitwise threshold
+// search over order-preserving integer keys and emits the ascending block list.
+#include "rf2_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// Order-preserving map float -> uint32 (larger float <=> larger key); -0 is folded into +0.
+__device__ __forceinline__ uint32_t order_key(float x) {
+  x = (x == 0.f) ? 0.f : x;
+  const uint32_t u = __float_as_uint(x);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ int popc64(unsigned long long m) { return __builtin_popcountll(m); }
+
+template <int D, int EMAX>
+__global__ void __launch_bounds__(256) predict_mask_kernel(
+    const float* __restrict__ qbar, const float* __restrict__ kbar, int32_t* __restrict__ blk_idx,
+    int32_t* __restrict__ blk_cnt, uint8_t* __restrict__ mask_dense, float* __restrict__ scores,
+    int Tb, int LD, int sink_begin, int sink_end, int k_row, int k_sel) {
+  extern __shared__ __attribute__((aligned(16))) float sc[];   // [16][LD]
+  const int bh = blockIdx.y;
+  const int i0 = blockIdx.x * 16;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lr = lane & 15, lk = lane >> 4;
+  const float* __restrict__ qb = qbar + (size_t)bh * Tb * D;
+  const float* __restrict__ kb = kbar + (size_t)bh * Tb * D;
+
+  // ---- scores: 16 x 16 tiles with v_mfma_f32_16x16x4_f32 -------------------------------
+  // Lane (lr, lk) feeds row lr of each operand.  Per 16 channels it loads 4 consecutive
+  // floats at 16*kk + 4*lk; MFMA step e uses element e, so "k slot lk" stands for channel
+  // 16*kk + 4*lk + e in both operands (a dot product does not care about summation order).
+  f32x4 a[D / 16];
+  {
+    const int row = min(i0 + lr, Tb - 1);
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) a[kk] = *reinterpret_cast<const f32x4*>(qb + (size_t)row * D + 16 * kk + 4 * lk);
+  }
+  const int n_ct = (Tb + 15) / 16;
+  for (int ct = wave; ct < n_ct; ct += 4) {
+    const int col = min(ct * 16 + lr, Tb - 1);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      const f32x4 b = *reinterpret_cast<const f32x4*>(kb + (size_t)col * D + 16 * kk + 4 * lk);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[kk][e], b[e], acc, 0, 0, 0);
+    }
+    // acc[i] = S_hat[i0 + 4*lk + i][ct*16 + lr]
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sc[(4 * lk + i) * LD + ct * 16 + lr] = acc[i];
+  }
+  __syncthreads();
+
+  if (scores != nullptr) {
+    for (int r = 0; r < 16 && i0 + r < Tb; ++r)
+      for (int j = threadIdx.x; j < Tb; j += 256)
+        scores[((size_t)bh * Tb + i0 + r) * Tb + j] = sc[r * LD + j];
+  }
+
+  // ---- selection: wavefront `wave` handles rows wave, wave+4, wave+8, wave+12 ------------
+  const int E = (Tb + 63) / 64;
+  const unsigned long long lt_mask = (1ull << lane) - 1ull;
+  for (int r = wave; r < 16; r += 4) {
+    const int i = i0 + r;
+    if (i >= Tb) break;
+    int32_t* __restrict__ out = blk_idx + ((size_t)bh * Tb + i) * k_row;
+    uint8_t* __restrict__ mrow = mask_dense ? mask_dense + ((size_t)bh * Tb + i) * Tb : nullptr;
+    if (i >= sink_begin && i < sink_end) {          // sink row: keeps every column
+      if (lane == 0) blk_cnt[(size_t)bh * Tb + i] = Tb;
+      for (int j = lane; j < k_row; j += 64) out[j] = j;
+      if (mrow) for (int j = lane; j < Tb; j += 64) mrow[j] = 1;
+      continue;
+    }
+    uint32_t key[EMAX];
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) {
+      const int j = 64 * e + lane;
+      const bool cand = (e < E) && (j < Tb) && !(j >= sink_begin && j < sink_end);
+      key[e] = cand ? order_key(sc[r * LD + j]) : 0u;   // 0 is below the key of every finite float
+    }
+    // Largest T with |{key >= T}| >= k_sel, built bit by bit: T is the k_sel-th largest key.
+    uint32_t T = 0xffffffffu;
+    if (k_sel > 0) {
+      T = 0u;
+      for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = T | (1u << bit);
+        int cnt = 0;
+#pragma unroll
+        for (int e = 0; e < EMAX; ++e)
+          if (e < E) cnt += popc64(__builtin_amdgcn_ballot_w64(key[e] >= cand));
+        if (cnt >= k_sel) T = cand;
+      }
+    }
+    int greater = 0;
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e)
+      if (e < E) greater += popc64(__builtin_amdgcn_ballot_w64(key[e] > T));
+    const int need_eq = k_sel - greater;              // equal keys to take, lowest column first
+    int eq_run = 0, out_run = 0;
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) {
+      if (e < E) {
+        const int j = 64 * e + lane;
+        const bool is_sink = (j < Tb) && (j >= sink_begin) && (j < sink_end);
+        const bool eq = (key[e] == T) && (k_sel > 0);
+        const unsigned long long eq_m = __builtin_amdgcn_ballot_w64(eq);
+        const bool sel = is_sink || (key[e] > T) || (eq && (eq_run + popc64(eq_m & lt_mask) < need_eq));
+        const unsigned long long sel_m = __builtin_amdgcn_ballot_w64(sel);
+        if (sel) out[out_run + popc64(sel_m & lt_mask)] = j;
+        if (mrow && j < Tb) mrow[j] = sel ? 1 : 0;
+        eq_run += popc64(eq_m);
+        out_run += popc64(sel_m);
+      }
+    }
+    if (lane == 0) blk_cnt[(size_t)bh * Tb + i] = out_run;   // == k_row by construction
+  }
+}
+
+}  // namespace
+
+extern "C" int rf2_predict_mask(const rf2_plan* plan, const float* qbar, const float* kbar, int32_t* blk_idx,
+                                int32_t* blk_cnt, uint8_t* mask_dense, float* scores, void* workspace,
+                                void* stream) {
+  (void)workspace;
+  if (!plan || !qbar || !kbar || !blk_idx || !blk_cnt) return RF2_ERR_INVALID_ARG;
+  if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
+  const rf2_config& c = plan->cfg;
+  const rf2_info& in = plan->info;
+  const int Tb = in.n_blocks;
+  const int E = (Tb + 63) / 64;
+  const int LD = E * 64 + 4;                        // +4: the 4 row groups of a tile store hit distinct banks
+  const size_t lds = (size_t)16 * LD * sizeof(float);
+  const dim3 grid((Tb + 15) / 16, c.batch * c.heads, 1);
+  hipStream_t st = (hipStream_t)stream;
+#define RF2_MASK_CASE(DD, EE)                                                                                   \
+  {                                                                                                             \
+    auto kern = predict_mask_kernel<DD, EE>;                                                                    \
+    if (lds > 48 * 1024)                                                                                        \
+      RF2_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));    \
+    kern<<<grid, 256, lds, st>>>(qbar, kbar, blk_idx, blk_cnt, mask_dense, scores, Tb, LD, in.sink_block_begin, \
+                                 in.sink_block_end, in.k_row, in.k_sel);                                        \
+    RF2_LAUNCH_CHECK();                                                                                         \
+    return RF2_OK;                                                                                              \
+  }
+  if (c.head_dim == 128) {
+    if (E <= 16) RF2_MASK_CASE(128, 16) else RF2_MASK_CASE(128, 32)
+  } else {
+    if (E <= 16) RF2_MASK_CASE(64, 16) else RF2_MASK_CASE(64, 32)
+  }
+#undef RF2_MASK_CASE
+}

@@ -1,0 +1,156 @@
+// Token permutation (Sec. 3.3 / 3.4) fused with block-mean pooling (Sec. 3.2, eqs. 5-6),
+// the key-major re-tiling of V for the attention kernel, and the inverse permutation.
+// All three kernels are pure HBM traffic: every row moves as 16-byte vectors, a group of
+// d/8 neighbouring lanes moving one whole row.
+#include "rf2_internal.h"
+
+namespace {
+
+typedef unsigned short u16;
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// One workgroup gathers one block of BLK permuted rows of Q (blockIdx.z = 0) or K (1),
+// writes them in permuted order and reduces their column sums to the block mean.
+template <int D, int BLK>
+__global__ void __launch_bounds__(256) permute_pool_kernel(
+    const uint4* __restrict__ q, const uint4* __restrict__ k, uint4* __restrict__ qp, uint4* __restrict__ kp,
+    float* __restrict__ qbar, float* __restrict__ kbar, const int32_t* __restrict__ perm,
+    int N, int n_blocks, int last_valid) {
+  constexpr int CH = D / 8;          // 16-byte chunks per row
+  constexpr int RG = 256 / CH;       // rows moved per pass
+  const int blk = blockIdx.x;
+  const int bh = blockIdx.y;
+  const uint4* __restrict__ src = (blockIdx.z == 0 ? q : k) + (size_t)bh * N * CH;
+  uint4* __restrict__ dst = (blockIdx.z == 0 ? qp : kp) + ((size_t)bh * n_blocks + blk) * BLK * CH;
+  float* __restrict__ mean = blockIdx.z == 0 ? qbar : kbar;
+  const int c = threadIdx.x % CH, rg = threadIdx.x / CH;
+
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int r = rg; r < BLK; r += RG) {
+    const int n = perm[blk * BLK + r];
+    uint4 x = make_uint4(0u, 0u, 0u, 0u);
+    if (n >= 0) x = src[(size_t)n * CH + c];
+    dst[r * CH + c] = x;
+    acc[0] += bf16_lo(x.x); acc[1] += bf16_hi(x.x);
+    acc[2] += bf16_lo(x.y); acc[3] += bf16_hi(x.y);
+    acc[4] += bf16_lo(x.z); acc[5] += bf16_hi(x.z);
+    acc[6] += bf16_lo(x.w); acc[7] += bf16_hi(x.w);
+  }
+  if (mean == nullptr) return;
+  __shared__ float part[RG][D + 1];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[rg][c * 8 + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < D) {
+    float s = 0.f;
+#pragma unroll
+    for (int g = 0; g < RG; ++g) s += part[g][threadIdx.x];   // fixed order: bit-reproducible
+    const int cnt = (blk == n_blocks - 1) ? last_valid : BLK;
+    mean[((size_t)bh * n_blocks + blk) * D + threadIdx.x] = s / (float)cnt;
+  }
+}
+
+// Position inside a 16-key group of the key-major V tile -> key offset (see rf2.h).
+__device__ __forceinline__ int rho(int r) { return (r & 3) | ((r & 4) << 1) | ((r & 8) >> 1); }
+
+// One workgroup gathers one block of BLK permuted rows of V into LDS and writes the
+// block as a [D][BLK] tile whose 16-key groups are stored in the order the attention
+// kernel's second matrix product reads them.
+template <int D, int BLK>
+__global__ void __launch_bounds__(256) permute_vtile_kernel(
+    const uint4* __restrict__ v, uint4* __restrict__ vp, const int32_t* __restrict__ perm, int N, int n_blocks) {
+  constexpr int CH = D / 8;
+  constexpr int RG = 256 / CH;
+  constexpr int PITCH = D + 2;       // u16 elements per LDS row: odd number of dwords
+  __shared__ __attribute__((aligned(16))) u16 tile[BLK * PITCH];
+  const int blk = blockIdx.x, bh = blockIdx.y;
+  const uint4* __restrict__ src = v + (size_t)bh * N * CH;
+  const int c = threadIdx.x % CH, rg = threadIdx.x / CH;
+  for (int r = rg; r < BLK; r += RG) {
+    const int n = perm[blk * BLK + r];
+    uint4 x = make_uint4(0u, 0u, 0u, 0u);
+    if (n >= 0) x = src[(size_t)n * CH + c];
+    uint32_t* row = reinterpret_cast<uint32_t*>(tile + r * PITCH + c * 8);  // 4-byte aligned: PITCH, c*8 even
+    row[0] = x.x; row[1] = x.y; row[2] = x.z; row[3] = x.w;
+  }
+  __syncthreads();
+  constexpr int OC = BLK / 8;        // 16-byte chunks per output row (one channel, BLK keys)
+  uint4* __restrict__ dst = vp + ((size_t)bh * n_blocks + blk) * D * OC;
+  for (int o = threadIdx.x; o < D * OC; o += 256) {
+    const int ch = o / OC, x8 = (o % OC) * 8;
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int s0 = x8 + 2 * e, s1 = s0 + 1;
+      const int k0 = (s0 & ~15) + rho(s0 & 15), k1 = (s1 & ~15) + rho(s1 & 15);
+      w[e] = (uint32_t)tile[k0 * PITCH + ch] | ((uint32_t)tile[k1 * PITCH + ch] << 16);
+    }
+    dst[o] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+// o[n] = op[inv[n]]: gathered reads, fully sequential writes.
+template <int D>
+__global__ void __launch_bounds__(256) unpermute_kernel(
+    const uint4* __restrict__ op, uint4* __restrict__ o, const int32_t* __restrict__ inv, int N, size_t N_pad) {
+  constexpr int CH = D / 8;
+  constexpr int RG = 256 / CH;
+  const int bh = blockIdx.y;
+  const uint4* __restrict__ src = op + (size_t)bh * N_pad * CH;
+  uint4* __restrict__ dst = o + (size_t)bh * N * CH;
+  const int c = threadIdx.x % CH, rg = threadIdx.x / CH;
+  const int n0 = blockIdx.x * 128;
+#pragma unroll 4
+  for (int r = rg; r < 128; r += RG) {
+    const int n = n0 + r;
+    if (n < N) dst[(size_t)n * CH + c] = src[(size_t)inv[n] * CH + c];
+  }
+}
+
+}  // namespace
+
+extern "C" int rf2_permute(const rf2_plan* plan, const void* q, const void* k, const void* v, void* qp, void* kp,
+                           void* vp, float* qbar, float* kbar, void* stream) {
+  if (!plan || !q || !k || !v || !qp || !kp || !vp) return RF2_ERR_INVALID_ARG;
+  if ((qbar == nullptr) != (kbar == nullptr)) return RF2_ERR_INVALID_ARG;
+  if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
+  const rf2_config& c = plan->cfg;
+  const rf2_info& in = plan->info;
+  hipStream_t st = (hipStream_t)stream;
+  const dim3 grid_qk(in.n_blocks, c.batch * c.heads, 2), grid_v(in.n_blocks, c.batch * c.heads, 1);
+#define RF2_PERMUTE_CASE(DD, BB)                                                                              \
+  if (c.head_dim == DD && c.block == BB) {                                                                    \
+    permute_pool_kernel<DD, BB><<<grid_qk, 256, 0, st>>>((const uint4*)q, (const uint4*)k, (uint4*)qp,        \
+                                                          (uint4*)kp, qbar, kbar, plan->d_perm, (int)in.N,     \
+                                                          in.n_blocks, in.last_block_valid);                   \
+    RF2_LAUNCH_CHECK();                                                                                       \
+    permute_vtile_kernel<DD, BB><<<grid_v, 256, 0, st>>>((const uint4*)v, (uint4*)vp, plan->d_perm, (int)in.N, \
+                                                          in.n_blocks);                                        \
+    RF2_LAUNCH_CHECK();                                                                                       \
+    return RF2_OK;                                                                                            \
+  }
+  RF2_PERMUTE_CASE(128, 128)
+  RF2_PERMUTE_CASE(64, 64)
+  RF2_PERMUTE_CASE(128, 64)
+  RF2_PERMUTE_CASE(64, 128)
+#undef RF2_PERMUTE_CASE
+  return RF2_ERR_UNSUPPORTED;
+}
+
+extern "C" int rf2_unpermute(const rf2_plan* plan, const void* op, void* o, void* stream) {
+  if (!plan || !op || !o) return RF2_ERR_INVALID_ARG;
+  if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
+  const rf2_config& c = plan->cfg;
+  const rf2_info& in = plan->info;
+  hipStream_t st = (hipStream_t)stream;
+  const dim3 grid((unsigned)((in.N + 127) / 128), c.batch * c.heads, 1);
+  if (c.head_dim == 128)
+    unpermute_kernel<128><<<grid, 256, 0, st>>>((const uint4*)op, (uint4*)o, plan->d_inv, (int)in.N, (size_t)in.N_pad);
+  else
+    unpermute_kernel<64><<<grid, 256, 0, st>>>((const uint4*)op, (uint4*)o, plan->d_inv, (int)in.N, (size_t)in.N_pad);
+  RF2_LAUNCH_CHECK();
+  return RF2_OK;
+}

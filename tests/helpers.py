@@ -1,0 +1,79 @@
+"""Shared helpers of the GPU parity tests (no test cases here)."""
+import numpy as np
+import torch
+
+from oracle import rf2_oracle as orc
+from paper_2512_24086_amd import inputs, rf2
+
+# Tolerances of the attention output vs. the fp64 oracle (bf16 operands, fp32 accumulation,
+# probabilities and outputs rounded to bf16: |O| <= max|V| ~ 4, bf16 half-ulp at 4 is 2^-7 = 7.8e-3).
+ATTN_MAX_ABS = 2e-2
+ATTN_MEAN_ABS = 2e-3
+TIE_GAP = 1e-3          # rows whose selection-boundary score gap is below this may differ
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    """Exact fp64 values of a bf16 tensor (through its bit pattern)."""
+    return orc.bf16_bits_to_f64(inputs.bf16_bits(t)).reshape(tuple(t.shape))
+
+
+def rho(r):
+    return (r & 3) | ((r & 4) << 1) | ((r & 8) >> 1)
+
+
+def vp_to_rows(vp: np.ndarray) -> np.ndarray:
+    """Decode the key-major V tiles [Tb, d, b] of one head into row-major [Tb*b, d]."""
+    Tb, d, b = vp.shape
+    s = np.arange(b)
+    key_of_pos = (s & ~15) + rho(s & 15)
+    out = np.empty((Tb, b, d), dtype=vp.dtype)
+    out[:, key_of_pos, :] = np.transpose(vp, (0, 2, 1))
+    return out.reshape(Tb * b, d)
+
+
+def lists_to_device(M_heads, k_row, Tb, device):
+    """Oracle masks [heads][Tb,Tb] -> (blk_idx [1,heads,Tb,k_row], blk_cnt [1,heads,Tb]) tensors."""
+    Hh = len(M_heads)
+    idx = np.zeros((1, Hh, Tb, k_row), dtype=np.int32)
+    cnt = np.zeros((1, Hh, Tb), dtype=np.int32)
+    for h, M in enumerate(M_heads):
+        for i in range(Tb):
+            cols = np.flatnonzero(M[i]).astype(np.int32)
+            if cols.size == Tb:
+                cnt[0, h, i] = Tb
+                idx[0, h, i, :] = np.arange(k_row)
+            else:
+                assert cols.size <= k_row
+                cnt[0, h, i] = cols.size
+                idx[0, h, i, :cols.size] = cols
+    return torch.from_numpy(idx).to(device), torch.from_numpy(cnt).to(device)
+
+
+def gpu_lists_to_mask(blk_idx, blk_cnt, Tb):
+    """Device lists of one head -> boolean [Tb,Tb]; checks the list format on the way."""
+    idx, cnt = blk_idx.cpu().numpy(), blk_cnt.cpu().numpy()
+    M = np.zeros((Tb, Tb), dtype=bool)
+    for i in range(Tb):
+        if cnt[i] == Tb:
+            M[i] = True
+        else:
+            cols = idx[i, :cnt[i]]
+            assert (np.diff(cols) > 0).all(), "block list must be strictly ascending"
+            assert cols.min() >= 0 and cols.max() < Tb
+            M[i, cols] = True
+    return M
+
+
+def make_plan(wl: inputs.Workload, sparsity=None, **kw):
+    args = dict(batch=wl.batch, heads=wl.heads, head_dim=wl.head_dim, T=wl.T, H=wl.H, W=wl.W, block=wl.block,
+                sparsity=wl.sparsity if sparsity is None else sparsity, sink_frames=wl.sink_frames)
+    args.update(kw)
+    return rf2.Plan(**args)
+
+
+def oracle_layer(wl, q, k, v, head, plan, q_blocks=None, sparsity=None):
+    c = plan.cfg
+    Q, K, V = (f64(x[0, head]) for x in (q, k, v))
+    return orc.layer(Q, K, V, T=c.T, H=c.H, W=c.W, block=c.block, sparsity=c.sparsity, sink_frames=c.sink_frames,
+                     sink_at_end=bool(c.sink_at_end), window=(plan.info.wt, plan.info.wh, plan.info.ww),
+                     budget_mode=c.budget_mode, q_blocks=q_blocks)

@@ -1,0 +1,151 @@
+"""GPU parity: every stage of the HIP path vs. the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rf2_oracle as orc
+from paper_2512_24086_amd import inputs
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+SMALL = {
+    # name: (workload, plan overrides)
+    "tiny": (inputs.WORKLOADS["tiny"], {}),
+    "tiny_sink_front": (inputs.WORKLOADS["tiny"], dict(sink_at_end=0)),
+    "tiny_dense": (inputs.WORKLOADS["tiny"], dict(sparsity=0.0)),
+    "ragged_d128_b128": (inputs.Workload("ragged", 6, 1, 3, 128, 5, 10, 13, 128, 0.5, 1, 0.3), {}),
+    "ragged_d128_b64": (inputs.Workload("ragged2", 7, 1, 2, 128, 4, 9, 11, 64, 0.6, 1, 0.3), dict(window=(2, 4, 4))),
+    "ragged_d64_b128": (inputs.Workload("ragged3", 8, 1, 2, 64, 3, 12, 15, 128, 0.4, 0, 0.3), {}),
+    "image_small": (inputs.Workload("img", 9, 1, 2, 128, 1, 40, 36, 128, 0.5, 0, 0.3), {}),
+    "one_block": (inputs.Workload("one", 10, 1, 1, 128, 1, 5, 7, 128, 0.5, 0, 0.3), {}),
+    "row_incl_sink": (inputs.WORKLOADS["tiny"], dict(budget_mode=1, sparsity=0.6)),
+}
+
+
+@pytest.fixture(scope="module", params=list(SMALL), ids=list(SMALL))
+def case(request):
+    wl, over = SMALL[request.param]
+    print(f"\n[case] {request.param}: {wl}", flush=True)
+    plan = hp.make_plan(wl, **over)
+    q, k, v = inputs.make_qkv(wl)
+    qd, kd, vd = (x.to(DEV) for x in (q, k, v))
+    buf = plan.alloc(DEV, dense_mask=True, scores=True, lse=True)
+    for t in buf.values():
+        t.fill_(0) if t.dtype != torch.bfloat16 else t.copy_(torch.full_like(t, float("nan")))
+    plan.layer(qd, kd, vd, buf)
+    torch.cuda.synchronize()
+    ref = [hp.oracle_layer(wl, q, k, v, h, plan) for h in range(wl.heads)]
+    yield wl, plan, (q, k, v), (qd, kd, vd), buf, ref
+    plan.close()
+
+
+def test_permute_is_bit_exact(case):
+    wl, plan, (q, k, v), _, buf, ref = case
+    N, Np = plan.info.N, plan.info.N_pad
+    for h in range(wl.heads):
+        for name, src in (("qp", q), ("kp", k)):
+            got = inputs.bf16_bits(buf[name][0, h])
+            want = inputs.bf16_bits(src[0, h])[ref[h]["perm"]]
+            assert np.array_equal(got[:N], want), name
+            assert (got[N:] == 0).all(), "padding rows must be zero"
+        got_v = hp.vp_to_rows(inputs.bf16_bits(buf["vp"][0, h]))
+        assert np.array_equal(got_v[:N], inputs.bf16_bits(v[0, h])[ref[h]["perm"]])
+        assert (got_v[N:] == 0).all()
+
+
+def test_block_means(case):
+    wl, plan, _, _, buf, ref = case
+    for h in range(wl.heads):
+        for name in ("qbar", "kbar"):
+            got = buf[name][0, h].double().cpu().numpy()
+            # fp32 sum of <=128 bf16 values of magnitude ~1, then one division
+            assert np.abs(got - ref[h][name]).max() < 2e-6, name
+
+
+def test_scores_and_block_mask(case):
+    wl, plan, _, _, buf, ref = case
+    i = plan.info
+    Tb = i.n_blocks
+    near_ties = 0
+    for h in range(wl.heads):
+        S = buf["scores"][0, h].double().cpu().numpy()
+        assert np.abs(S - ref[h]["S_hat"]).max() < 1e-4          # fp32 dot products of length d, |S| ~ 10
+        M = hp.gpu_lists_to_mask(buf["blk_idx"][0, h], buf["blk_cnt"][0, h], Tb)
+        assert np.array_equal(M, buf["mask_dense"][0, h].cpu().numpy().astype(bool)), "list and dense mask disagree"
+        cnt = buf["blk_cnt"][0, h].cpu().numpy()
+        sink = np.zeros(Tb, dtype=bool)
+        sink[i.sink_block_begin:i.sink_block_end] = True
+        assert (cnt[sink] == Tb).all() and (cnt[~sink] == (i.k_row if i.k_row < Tb else Tb)).all()
+        assert M[:, sink].all() and M[sink].all()
+        clear = ref[h]["gap"] > hp.TIE_GAP
+        near_ties += int((~clear & ~sink).sum())
+        assert np.array_equal(M[clear], ref[h]["M"][clear]), "mask differs on a row with a clear boundary"
+        assert (M.sum(1) == ref[h]["M"].sum(1)).all()
+    print(f"[mask] near-tie rows exempted: {near_ties}")
+
+
+def test_attention_with_oracle_mask(case):
+    """Feeds the ORACLE's block lists to the kernel, isolating the attention arithmetic."""
+    wl, plan, _, _, buf, ref = case
+    i = plan.info
+    idx, cnt = hp.lists_to_device([r["M"] for r in ref], i.k_row, i.n_blocks, DEV)
+    op = torch.full_like(buf["op"], float("nan"))
+    lse = torch.zeros_like(buf["lse"])
+    plan.rf2_block_sparse_attn(buf["qp"], buf["kp"], buf["vp"], idx, cnt, op, lse)
+    torch.cuda.synchronize()
+    for h in range(wl.heads):
+        got = hp.f64(op[0, h])[:i.N]
+        err = np.abs(got - ref[h]["Op"])
+        assert err.max() <= hp.ATTN_MAX_ABS and err.mean() <= hp.ATTN_MEAN_ABS, (err.max(), err.mean())
+        got_lse = lse[0, h, :i.N].double().cpu().numpy()
+        assert np.abs(got_lse - ref[h]["lse"]).max() < 2e-3
+
+
+def test_whole_layer_and_unpermute(case):
+    wl, plan, _, _, buf, ref = case
+    i = plan.info
+    for h in range(wl.heads):
+        op_bits = inputs.bf16_bits(buf["op"][0, h])[:i.N]
+        o_bits = inputs.bf16_bits(buf["o"][0, h])
+        assert np.array_equal(o_bits[ref[h]["perm"]], op_bits), "unpermute must be a bit-exact scatter"
+        M = hp.gpu_lists_to_mask(buf["blk_idx"][0, h], buf["blk_cnt"][0, h], i.n_blocks)
+        if np.array_equal(M, ref[h]["M"]):
+            want = ref[h]["O"]
+        else:                                  # near-tie rows chose differently: oracle attention on the GPU's mask
+            Op = orc.block_sparse_attention(ref[h]["Qp"], ref[h]["Kp"], ref[h]["Vp"], M, plan.cfg.block)
+            want = orc.unpermute(Op, ref[h]["perm"])
+        err = np.abs(hp.f64(buf["o"][0, h]) - want)
+        assert err.max() <= hp.ATTN_MAX_ABS and err.mean() <= hp.ATTN_MEAN_ABS, (err.max(), err.mean())
+
+
+def test_round_trip_is_identity():
+    wl = inputs.WORKLOADS["tiny"]
+    plan = hp.make_plan(wl)
+    q, k, v = (x.to(DEV) for x in inputs.make_qkv(wl))
+    buf = plan.alloc(DEV)
+    plan.rf2_permute(q, k, v, buf["qp"], buf["kp"], buf["vp"])          # no pooling requested
+    plan.rf2_unpermute(buf["qp"], buf["o"])
+    torch.cuda.synchronize()
+    assert torch.equal(buf["o"].view(torch.int16), q.view(torch.int16))
+    plan.close()
+
+
+def test_dense_layer_is_independent_of_the_permutation():
+    """At sparsity 0 the layer is plain attention: window shape and sink placement cannot matter."""
+    wl = inputs.Workload("inv", 11, 1, 2, 128, 4, 9, 11, 128, 0.0, 1, 0.3)
+    q, k, v = inputs.make_qkv(wl)
+    qd, kd, vd = (x.to(DEV) for x in (q, k, v))
+    outs = []
+    for over in (dict(), dict(window=(1, 3, 5), sink_at_end=0), dict(window=(4, 9, 11), sink_frames=0)):
+        plan = hp.make_plan(wl, **over)
+        buf = plan.alloc(DEV)
+        outs.append(hp.f64(plan.layer(qd, kd, vd, buf)))
+        torch.cuda.synchronize()
+        plan.close()
+    dense = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(hp.f64(q)), torch.from_numpy(hp.f64(k)), torch.from_numpy(hp.f64(v))).numpy()
+    for o in outs:
+        err = np.abs(o - dense)
+        assert err.max() <= hp.ATTN_MAX_ABS and err.mean() <= hp.ATTN_MEAN_ABS

@@ -1,0 +1,108 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and its
+host logic (config validation, sizes, permutation tables) agrees with the oracle."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import rf2_oracle as orc
+from paper_2512_24086_amd import rf2
+from paper_2512_24086_amd.inputs import WORKLOADS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "rf2.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rf2_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = rf2.lib()
+    names = declared_symbols()
+    assert set(names) == set(rf2.SIGNATURES), "binding and header disagree on the entry points"
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert lib.rf2_version() >= 100
+    assert lib.rf2_strerror(0) == b"ok" and b"invalid" in lib.rf2_strerror(-1)
+
+
+def make_plan(**kw):
+    base = dict(batch=1, heads=2, head_dim=64, T=6, H=16, W=16, block=64, sparsity=0.5, sink_frames=1)
+    base.update(kw)
+    return rf2.Plan(**base)
+
+
+@pytest.mark.parametrize("bad", [
+    dict(batch=0), dict(heads=0), dict(T=0), dict(sink_frames=6), dict(sink_frames=-1), dict(sparsity=1.0),
+    dict(sparsity=-0.1), dict(sparsity=float("nan")), dict(budget_mode=3), dict(window=(0, 4, 4)),
+    dict(window=(-1, 4, 4)), dict(sink_at_end=2),
+])
+def test_invalid_configs_are_rejected(bad):
+    with pytest.raises(rf2.Rf2Error) as e:
+        make_plan(**bad)
+    assert e.value.code == rf2.RF2_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("bad", [dict(head_dim=96), dict(block=32), dict(T=4096, H=256, W=256)])
+def test_unsupported_configs_are_rejected(bad):
+    with pytest.raises(rf2.Rf2Error) as e:
+        make_plan(**bad)
+    assert e.value.code == rf2.RF2_ERR_UNSUPPORTED
+
+
+def test_null_arguments_are_rejected():
+    lib = rf2.lib()
+    assert lib.rf2_plan_create(None, None) == rf2.RF2_ERR_INVALID_ARG
+    assert lib.rf2_plan_info(None, None) == rf2.RF2_ERR_INVALID_ARG
+    assert lib.rf2_permute(*([None] * 10)) == rf2.RF2_ERR_INVALID_ARG
+    assert lib.rf2_predict_mask(*([None] * 9)) == rf2.RF2_ERR_INVALID_ARG
+    assert lib.rf2_block_sparse_attn(*([None] * 9)) == rf2.RF2_ERR_INVALID_ARG
+    assert lib.rf2_unpermute(*([None] * 4)) == rf2.RF2_ERR_INVALID_ARG
+    assert lib.rf2_plan_destroy(None) == rf2.RF2_OK
+
+
+@pytest.mark.parametrize("name", list(WORKLOADS))
+def test_plan_sizes_and_tables_match_the_oracle(name):
+    wl = WORKLOADS[name]
+    for s in (wl.sweep or (wl.sparsity,)):
+        p = make_plan(batch=wl.batch, heads=wl.heads, head_dim=wl.head_dim, T=wl.T, H=wl.H, W=wl.W,
+                      block=wl.block, sparsity=s, sink_frames=wl.sink_frames)
+        i = p.info
+        Tb = orc.n_blocks(wl.N, wl.block)
+        sb, se = orc.sink_block_range(wl.N, wl.H * wl.W, wl.block, wl.sink_frames, True)
+        k_row, k_sel = orc.budget(Tb, se - sb, s)
+        assert (i.N, i.n_blocks, i.N_pad) == (wl.N, Tb, Tb * wl.block)
+        assert i.last_block_valid == wl.N - (Tb - 1) * wl.block
+        assert (i.sink_block_begin, i.sink_block_end) == (sb, se)
+        assert (i.k_row, i.k_sel) == (k_row, k_sel)
+        assert i.kept_pairs_per_head == orc.kept_pairs(Tb, se - sb, k_row)
+        assert abs(i.achieved_sparsity - (1 - i.kept_pairs_per_head / Tb ** 2)) < 1e-12
+        assert (i.wt, i.wh, i.ww) == orc.default_window(wl.block, wl.T > 1)
+    perm, inv = p.rf2_plan_perm()
+    want = orc.perm_table(wl.T, wl.H, wl.W, i.wt, i.wh, i.ww, wl.sink_frames, True)
+    assert np.array_equal(perm, want)                      # bit-exact index parity
+    assert np.array_equal(inv, orc.inverse_table(want))
+    p.close()
+
+
+@pytest.mark.parametrize("case", [
+    (5, 7, 9, (2, 4, 4), 1, 1), (5, 7, 9, (2, 4, 4), 1, 0), (5, 7, 9, (3, 2, 5), 0, 1), (4, 5, 3, (3, 2, 2), 2, 1),
+    (1, 10, 13, (1, 8, 16), 0, 1), (7, 3, 5, (2, 2, 3), 3, 0),
+])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_ragged_tables_and_budget_modes(case, mode):
+    T, H, W, win, sf, at_end = case
+    p = make_plan(T=T, H=H, W=W, window=win, sink_frames=sf, sink_at_end=at_end, sparsity=0.6, budget_mode=mode,
+                  block=64, head_dim=64)
+    perm, inv = p.rf2_plan_perm()
+    want = orc.perm_table(T, H, W, *win, sf, bool(at_end))
+    assert np.array_equal(perm, want)
+    i = p.info
+    sb, se = orc.sink_block_range(T * H * W, H * W, 64, sf, bool(at_end))
+    assert (i.sink_block_begin, i.sink_block_end) == (sb, se)
+    assert (i.k_row, i.k_sel) == orc.budget(i.n_blocks, se - sb, 0.6, mode)
+    p.close()
