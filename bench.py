@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the RainFusion2.0 attention layer on one MI355X.
+
+A "step" is one pass of the whole layer -- permute+pool, mask prediction, block-sparse
+attention, unpermute -- over one synthetic batch of the headline workload (720p video DiT:
+1 x 40 heads x d128, 21x45x80 = 75,600 tokens, block 128, sparsity 0.8, first-frame sink).
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu] [--no-dense]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2512_24086_amd import inputs, rf2  # noqa: E402
+
+METRIC = "ms/layer + effective TFLOPS of block-sparse attn @80% sparsity, 75.6K tokens"
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+# HBM bytes per launch of the attention kernel on the headline workload, from the rocprofv3 --pmc
+# runs summarised in profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel); None = not measured.
+ATTN_TRAFFIC_BYTES = {"video720p": None}
+
+
+def ensure_library():
+    if not os.path.exists(rf2.LIB_PATH):
+        from paper_2512_24086_amd.build import build
+        build(verbose=False)
+    rf2.lib()
+
+
+def time_layer(plan, q, k, v, buf, steps, warmup):
+    """Times `steps` whole layers (wall clock between device syncs) and each stage (events)."""
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+
+    def one(marks=None):
+        if marks: marks[0].record()
+        plan.rf2_permute(q, k, v, buf["qp"], buf["kp"], buf["vp"], buf["qbar"], buf["kbar"])
+        if marks: marks[1].record()
+        plan.rf2_predict_mask(buf["qbar"], buf["kbar"], buf["blk_idx"], buf["blk_cnt"])
+        if marks: marks[2].record()
+        plan.rf2_block_sparse_attn(buf["qp"], buf["kp"], buf["vp"], buf["blk_idx"], buf["blk_cnt"], buf["op"])
+        if marks: marks[3].record()
+        plan.rf2_unpermute(buf["op"], buf["o"])
+        if marks: marks[4].record()
+
+    for _ in range(warmup):
+        one()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        one(ev[s])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    names = ["permute_pool", "predict_mask", "block_sparse_attn", "unpermute"]
+    stages = {n: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(steps)) / steps
+              for i, n in enumerate(names)}
+    return wall_ms, stages
+
+
+def time_attn_only(plan, buf, idx, cnt, iters, warmup=1):
+    for _ in range(warmup):
+        plan.rf2_block_sparse_attn(buf["qp"], buf["kp"], buf["vp"], idx, cnt, buf["op"])
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        plan.rf2_block_sparse_attn(buf["qp"], buf["kp"], buf["vp"], idx, cnt, buf["op"])
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def time_sdpa(q, k, v, iters=2):
+    """Library dense attention on the same GPU (context for the dense side of the speedup)."""
+    try:
+        f = torch.nn.functional.scaled_dot_product_attention
+        f(q, k, v)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            f(q, k, v)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters
+    except Exception as e:  # noqa: BLE001 -- report, never fail the bench on the context number
+        return f"unavailable: {type(e).__name__}"
+
+
+def cpu_baseline(wl, plan, q, k, v, dense_flops):
+    """The fp64 oracle, untuned, on a bounded sample: all stages for ONE head up to the mask, attention
+    for a few Q blocks of that head; extrapolated to the whole layer by head count and kept pairs."""
+    from oracle import rf2_oracle as orc
+    from threadpoolctl import threadpool_info
+    import numpy as np
+    i, c = plan.info, plan.cfg
+    head = 0
+    Q, K, V = (orc.bf16_bits_to_f64(inputs.bf16_bits(x[0, head])) for x in (q, k, v))
+    t0 = time.perf_counter()
+    perm = orc.perm_table(c.T, c.H, c.W, i.wt, i.wh, i.ww, c.sink_frames, bool(c.sink_at_end))
+    Qp, Kp, Vp = orc.permute(Q, perm), orc.permute(K, perm), orc.permute(V, perm)
+    S_hat = orc.block_scores(orc.pool_blocks(Qp, c.block), orc.pool_blocks(Kp, c.block))
+    M = orc.select_blocks(S_hat, i.k_sel, i.sink_block_begin, i.sink_block_end)
+    t_pre = time.perf_counter() - t0
+    Tb = i.n_blocks
+    rng = np.random.default_rng(0)
+    sample = sorted({0, Tb - 1, i.sink_block_begin, *rng.integers(0, Tb, 5).tolist()})
+    t0 = time.perf_counter()
+    Op = orc.block_sparse_attention(Qp, Kp, Vp, M, c.block, q_blocks=sample)
+    t_attn = time.perf_counter() - t0
+    pairs = int(sum(M[r].sum() for r in sample))
+    t_unp0 = time.perf_counter()
+    orc.unpermute(Op, perm)
+    t_unp = time.perf_counter() - t_unp0
+    per_head = t_pre + t_unp + t_attn * (i.kept_pairs_per_head / pairs)
+    layer_s = per_head * c.batch * c.heads
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": dense_flops / layer_s / 1e12, "unit": "TFLOP/s dense-equivalent (extrapolated)",
+            "cores": threads, "kind": "oracle", "ms_per_layer_extrapolated": layer_s * 1e3,
+            "sample": f"head {head}: permute+pool+scores+selection in full ({t_pre:.2f} s), attention on "
+                      f"{len(sample)} of {Tb} Q blocks = {pairs} block pairs ({t_attn:.2f} s), scaled by "
+                      f"kept pairs and by {c.batch * c.heads} heads"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="video720p", choices=list(inputs.WORKLOADS))
+    ap.add_argument("--sparsity", type=float, default=None)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention baselines")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is a single-GPU kernel path; run with --gpus 1 "
+              "(heads shard across GPUs with no communication, nothing multi-GPU is implemented)", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    ensure_library()
+    torch.cuda.set_device(0)
+    wl = inputs.WORKLOADS[args.workload]
+    s = wl.sparsity if args.sparsity is None else args.sparsity
+    plan = rf2.Plan(batch=wl.batch, heads=wl.heads, head_dim=wl.head_dim, T=wl.T, H=wl.H, W=wl.W, block=wl.block,
+                    sparsity=s, sink_frames=wl.sink_frames)
+    i = plan.info
+    q, k, v = inputs.make_qkv(wl, device="cuda")
+    buf = plan.alloc("cuda")
+    torch.cuda.synchronize()
+
+    wall_ms, stages = time_layer(plan, q, k, v, buf, args.steps, args.warmup)
+    bh = wl.batch * wl.heads
+    dense_flops = 4.0 * wl.N * wl.N * wl.head_dim * bh
+    kept_flops = 4.0 * wl.block * wl.block * wl.head_dim * i.kept_pairs_per_head * bh
+    attn_ms = stages["block_sparse_attn"]
+    itemsize = 2
+    tensor_bytes = bh * wl.N * wl.head_dim * itemsize
+    gbps = {
+        "permute_pool": (6 * tensor_bytes) / (stages["permute_pool"] * 1e-3) / 1e9,
+        "unpermute": (2 * tensor_bytes) / (stages["unpermute"] * 1e-3) / 1e9,
+    }
+    out = {
+        "metric": METRIC, "value": dense_flops / (wall_ms * 1e-3) / 1e12,
+        "unit": "TFLOP/s dense-equivalent (4*N^2*d*heads per layer / whole-layer time)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B{wl.batch} x {wl.heads} heads x d{wl.head_dim}, grid {wl.T}x{wl.H}x{wl.W}"
+                               f" = {wl.N} tokens, block {wl.block}, sparsity {s}, sink_frames {wl.sink_frames}",
+                   "n_blocks": i.n_blocks, "k_row": i.k_row, "kept_pairs_per_head": i.kept_pairs_per_head,
+                   "achieved_sparsity": round(i.achieved_sparsity, 4)},
+        "stages_ms": {n: round(t, 4) for n, t in stages.items()},
+        "stages_gbps": {n: round(g, 1) for n, g in gbps.items()},
+        "attn": {"ms": round(attn_ms, 4), "kept_tflops": round(kept_flops / (attn_ms * 1e-3) / 1e12, 1),
+                 "dense_equiv_tflops": round(dense_flops / (attn_ms * 1e-3) / 1e12, 1)},
+        "roofline": {"bound": "mfma", "kernel": "block_sparse_attn_kernel",
+                     "achieved": kept_flops / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": kept_flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "traffic": ATTN_TRAFFIC_BYTES.get(wl.name) if args.sparsity is None else None},
+    }
+    if not args.no_dense:
+        cnt_dense = torch.full_like(buf["blk_cnt"], i.n_blocks)
+        dense_ms = time_attn_only(plan, buf, buf["blk_idx"], cnt_dense, iters=2)
+        sdpa_ms = time_sdpa(q, k, v)
+        best = min(dense_ms, sdpa_ms) if isinstance(sdpa_ms, float) else dense_ms
+        out["attn"].update({"dense_same_kernel_ms": round(dense_ms, 3),
+                            "dense_torch_sdpa_ms": round(sdpa_ms, 3) if isinstance(sdpa_ms, float) else sdpa_ms,
+                            "speedup_vs_fastest_dense": round(best / attn_ms, 3)})
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(wl, plan, q, k, v, dense_flops)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
