@@ -13,6 +13,9 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 
 // One workgroup gathers one block of BLK permuted rows of Q (blockIdx.z = 0) or K (1),
 // writes them in permuted order and reduces their column sums to the block mean.
+// Q rows stay row-major; a K block is written as an operand tile [D/8][BLK][8]: the
+// 16-byte chunk c of row r lands at chunk slot c*BLK + r, the order in which the attention
+// kernel's matrix-core operand reads walk it.
 template <int D, int BLK>
 __global__ void __launch_bounds__(256) permute_pool_kernel(
     const uint4* __restrict__ q, const uint4* __restrict__ k, uint4* __restrict__ qp, uint4* __restrict__ kp,
@@ -33,7 +36,7 @@ __global__ void __launch_bounds__(256) permute_pool_kernel(
     const int n = perm[blk * BLK + r];
     uint4 x = make_uint4(0u, 0u, 0u, 0u);
     if (n >= 0) x = src[(size_t)n * CH + c];
-    dst[r * CH + c] = x;
+    dst[blockIdx.z == 0 ? r * CH + c : c * BLK + r] = x;
     acc[0] += bf16_lo(x.x); acc[1] += bf16_hi(x.x);
     acc[2] += bf16_lo(x.y); acc[3] += bf16_hi(x.y);
     acc[4] += bf16_lo(x.z); acc[5] += bf16_hi(x.z);
@@ -57,8 +60,9 @@ __global__ void __launch_bounds__(256) permute_pool_kernel(
 __device__ __forceinline__ int rho(int r) { return (r & 3) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
 // One workgroup gathers one block of BLK permuted rows of V into LDS and writes the
-// block as a [D][BLK] tile whose 16-key groups are stored in the order the attention
-// kernel's second matrix product reads them.
+// block as the operand tile [BLK/8][D][8] of the attention kernel's second product:
+// 16-byte chunk (g, ch) holds channel ch of 8 keys of the block, chunks 2G and 2G+1
+// covering the 16-key group G in the order 0-3, 8-11 | 4-7, 12-15.
 template <int D, int BLK>
 __global__ void __launch_bounds__(256) permute_vtile_kernel(
     const uint4* __restrict__ v, uint4* __restrict__ vp, const int32_t* __restrict__ perm, int N, int n_blocks) {
@@ -77,14 +81,14 @@ __global__ void __launch_bounds__(256) permute_vtile_kernel(
     row[0] = x.x; row[1] = x.y; row[2] = x.z; row[3] = x.w;
   }
   __syncthreads();
-  constexpr int OC = BLK / 8;        // 16-byte chunks per output row (one channel, BLK keys)
+  constexpr int OC = BLK / 8;        // key chunks per block
   uint4* __restrict__ dst = vp + ((size_t)bh * n_blocks + blk) * D * OC;
   for (int o = threadIdx.x; o < D * OC; o += 256) {
-    const int ch = o / OC, x8 = (o % OC) * 8;
+    const int g = o / D, ch = o % D;   // consecutive lanes -> consecutive channels: contiguous 16-byte stores
     uint32_t w[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int s0 = x8 + 2 * e, s1 = s0 + 1;
+      const int s0 = 8 * g + 2 * e, s1 = s0 + 1;
       const int k0 = (s0 & ~15) + rho(s0 & 15), k1 = (s1 & ~15) + rho(s1 & 15);
       w[e] = (uint32_t)tile[k0 * PITCH + ch] | ((uint32_t)tile[k1 * PITCH + ch] << 16);
     }

@@ -21,13 +21,21 @@ def rho(r):
     return (r & 3) | ((r & 4) << 1) | ((r & 8) >> 1)
 
 
+def kp_to_rows(kp: np.ndarray) -> np.ndarray:
+    """Decode the K operand tiles [Tb, d/8, b, 8] of one head into row-major [Tb*b, d]."""
+    Tb, C, b, _ = kp.shape
+    return np.transpose(kp, (0, 2, 1, 3)).reshape(Tb * b, C * 8)
+
+
 def vp_to_rows(vp: np.ndarray) -> np.ndarray:
-    """Decode the key-major V tiles [Tb, d, b] of one head into row-major [Tb*b, d]."""
-    Tb, d, b = vp.shape
-    s = np.arange(b)
+    """Decode the V operand tiles [Tb, b/8, d, 8] of one head into row-major [Tb*b, d]."""
+    Tb, G, d, _ = vp.shape
+    b = G * 8
+    s = np.arange(b)                                  # storage position inside the block: chunk g = s//8, e = s%8
     key_of_pos = (s & ~15) + rho(s & 15)
-    out = np.empty((Tb, b, d), dtype=vp.dtype)
-    out[:, key_of_pos, :] = np.transpose(vp, (0, 2, 1))
+    by_pos = np.transpose(vp, (0, 1, 3, 2)).reshape(Tb, b, d)      # [Tb, position, channel]
+    out = np.empty_like(by_pos)
+    out[:, key_of_pos, :] = by_pos
     return out.reshape(Tb * b, d)
 
 
