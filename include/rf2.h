@@ -103,17 +103,21 @@ int rf2_plan_perm(const rf2_plan* plan, int32_t* perm_host, int32_t* inv_host);
  * Sec. 3.3 permutation of Q, K, V fused with the block means of eqs. (5), (6).
  *   q, k, v : [B, Hh, N, d] bf16, tokens in [T, H, W] raster order        (in)
  *   qp      : [B, Hh, N_pad, d] bf16, qp[p] = q[perm[p]]; rows >= N zero  (out)
- *   kp      : [B, Hh, Tb, d/8, b, 8] bf16 operand tiles: element (blk, c, r, e) is
- *             channel 8c+e of the permuted key row blk*b + r; rows >= N zero (out)
- *   vp      : [B, Hh, Tb, b/8, d, 8] bf16 operand tiles: element (blk, g, ch, e) is
- *             channel ch of the permuted value row
- *                 blk*b + 16*(g/2) + rho(8*(g%2) + e),
+ *   kp      : [B, Hh, Tb, b/64, d/8, 64, 8] bf16 operand tiles.  With KH = b/2, channel
+ *             8c+e of the permuted key row blk*b + r is element
+ *                 (blk, part = (r % KH) / 32, c, (r / KH)*32 + r % 32, e);
+ *             rows >= N zero                                               (out)
+ *   vp      : [B, Hh, Tb, b/64, 8, d, 8] bf16 operand tiles.  Inside a block the keys
+ *             take storage positions s = 0..b-1, position s holding block row
+ *                 16*(s/16) + rho(s%16),
  *             rho(r) = r for r in 0..3 and 12..15, r+4 for 4..7, r-4 for 8..11
  *             (each 16-key group is stored in the order 0-3, 8-11, 4-7, 12-15);
+ *             channel ch of position s is element
+ *                 (blk, part = (s % KH) / 32, g = (s / KH)*4 + (s % 32) / 8, ch, s % 8);
  *             rows >= N zero                                               (out)
  *             kp and vp are the layouts the attention kernel's matrix-core operand
- *             reads consume: a block is one contiguous b*d*2-byte tile that is copied
- *             to on-chip memory verbatim.
+ *             reads consume: every part (64 keys x d, contiguous) is copied to
+ *             on-chip memory verbatim.  For b = 64 there is one part per block.
  *   qbar, kbar : [B, Hh, Tb, d] fp32 means over the valid rows of each block of
  *             qp / kp (the last block divides by last_block_valid).  Pass both
  *             NULL to skip pooling.                                        (out)

@@ -17,6 +17,13 @@
 // exactly one B operand of the second product provided the A operand (V^T) lists the keys
 // of each 16-key group in the order 0-3, 8-11, 4-7, 12-15 -- the order rf2_permute writes.
 // Row statistics are per lane (one query column) plus one exchange with lane l^32.
+//
+// The loop is software-pipelined over "units" (one 32-key tile per wavefront, i.e. a
+// K/V block is KT = BLK/64 units): step s issues the matrix products S_{s+1} and
+// O += V P_{s-1} around the softmax arithmetic of unit s, so the matrix cores and the
+// vector ALU of a SIMD work at the same time although only one wavefront lives on it.
+// K and V unit parts stream from global memory straight into two 4-deep LDS rings, three
+// steps ahead of their use, with one barrier per step.
 #include "rf2_internal.h"
 
 namespace {
@@ -30,30 +37,50 @@ struct AttnCfg {
   static constexpr int NW = BLK / 32;           // wavefronts: (BLK/64 query halves) x (2 key halves)
   static constexpr int NT = NW * 64;
   static constexpr int KH = BLK / 2;            // keys per wavefront per block
-  static constexpr int KT = KH / 32;            // 32-key tiles per wavefront
+  static constexpr int KT = KH / 32;            // units (32-key tiles per wavefront) per block
   static constexpr int QT = 2;                  // 32-query tiles per wavefront
   static constexpr int DS = D / 16;             // k-steps of the first product
   static constexpr int DT = D / 32;             // 32-channel tiles of the output
-  static constexpr int KS = KH / 16;            // k-steps of the second product
   static constexpr int TILE_BYTES = BLK * D * 2;
-  static constexpr int DMA = TILE_BYTES / 1024 / NW;   // 1 KiB direct-to-LDS loads per wavefront per tile
+  static constexpr int UNIT_BYTES = TILE_BYTES / KT;   // K (or V^T) part of one unit: 64 keys x D
+  static constexpr int LPW = UNIT_BYTES / 1024 / NW;   // 1 KiB direct-to-LDS loads per wavefront per unit part
+  static constexpr int PENDING = 2 * 2 * LPW;          // loads a wavefront issues in two steps
+  static_assert(LPW >= 1 && PENDING < 63, "vmcnt range");
 };
 
-// K and V^T blocks are stored in global memory as operand tiles (see rf2.h): chunk-major
-// [chunk][row][8 bf16], TILE_BYTES contiguous.  A tile goes straight from global memory
-// into LDS, unchanged: each wavefront-wide load deposits 64 x 16 B at consecutive LDS
-// addresses, wavefront w taking KiB u*NW + w of the tile for u = 0..NDMA-1.  In LDS the
-// 16 lanes of a quarter-wave then read the same chunk of 16 consecutive rows = 256
-// contiguous bytes (no bank conflicts), and all reads of a product share one per-lane
-// base address plus compile-time offsets.
-template <int NW, int NDMA>
-__device__ __forceinline__ void dma_tile(unsigned char* lds_tile, const unsigned char* gtile, int wave, uint32_t tid16) {
+// rf2_permute stores every K and V^T block as KT contiguous unit parts in exactly the
+// order the operand reads below walk them ([chunk][64 rows][8 bf16], see rf2.h), so a
+// part is copied verbatim: each wavefront-wide load deposits 64 x 16 B at consecutive
+// LDS addresses (M0 = LDS base of that KiB), wavefront w taking KiB u*NW + w for
+// u = 0..LPW-1.  In LDS the 16 lanes of a quarter-wave read 16 consecutive 16-byte slots
+// (no bank conflicts) and all reads of a product share one per-lane base address plus
+// compile-time offsets.
+// The load is written in assembly on purpose: the compiler then does not track it, and
+// the only waits for it are the explicit vmcnt waits of ring_barrier below (its own
+// bookkeeping of direct-to-LDS loads runs out of slots with eight ring buffers and falls
+// back to waiting for every outstanding load before unrelated LDS reads).
+template <int NW, int LPW>
+__device__ __forceinline__ void dma_unit(unsigned char* lds, const unsigned char* g, int wave, uint32_t tid16) {
+  const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
 #pragma unroll
-  for (int u = 0; u < NDMA; ++u) {
-    __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)(gtile + u * (NW * 1024) + tid16),
-        (__attribute__((address_space(3))) void*)(lds_tile + (u * NW + wave) * 1024), 16, 0, 0);
+  for (int u = 0; u < LPW; ++u) {
+    const uint32_t m0 = lds_base + (uint32_t)((u * NW + wave) * 1024);
+    const unsigned char* src = g + u * (NW * 1024) + tid16;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m0), "v"(src) : "memory");
   }
+}
+
+// Workgroup barrier of the steady-state loop: waits until at most N of this wavefront's
+// direct-to-LDS loads are still in flight, then s_barrier.  __syncthreads() cannot be used
+// there: its release fence would wait for ALL outstanding loads, i.e. also for the parts
+// prefetched for later steps.  LDS operand reads have completed before the barrier because
+// the MFMAs consuming them were issued; the asm memory clobbers keep the compiler from
+// moving LDS accesses across.
+template <int N>
+__device__ __forceinline__ void ring_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 }
 
 template <int D, int BLK>
@@ -63,14 +90,16 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     float* __restrict__ lse, const int32_t* __restrict__ row_order, int rows_per_xcd, int Tb, int k_row,
     int last_valid, float scale_log2) {
   using C = AttnCfg<D, BLK>;
-  // Two K and two V^T buffers.  They are separate objects on purpose: the compiler then
-  // knows that a direct-to-LDS load into one buffer does not alias reads of another and
-  // does not wait for it.
-  __shared__ __attribute__((aligned(1024))) unsigned char KsA[C::TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) unsigned char KsB[C::TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) unsigned char VsA[C::TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) unsigned char VsB[C::TILE_BYTES];
-  __shared__ float ml[(BLK / 64) * 2 * C::QT * 2 * 64];   // [wa][wc][qt][m|l][lane]
+  // Rings of 4 K parts and 4 V^T parts.
+  __shared__ __attribute__((aligned(1024))) unsigned char ring[8 * C::UNIT_BYTES];
+  unsigned char* const K0 = ring;
+  unsigned char* const K1 = ring + 1 * C::UNIT_BYTES;
+  unsigned char* const K2 = ring + 2 * C::UNIT_BYTES;
+  unsigned char* const K3 = ring + 3 * C::UNIT_BYTES;
+  unsigned char* const V0 = ring + 4 * C::UNIT_BYTES;
+  unsigned char* const V1 = ring + 5 * C::UNIT_BYTES;
+  unsigned char* const V2 = ring + 6 * C::UNIT_BYTES;
+  unsigned char* const V3 = ring + 7 * C::UNIT_BYTES;
 
   // ---- which Q block ---------------------------------------------------------------
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -82,6 +111,7 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
   const bool dense = (cnt == Tb);
   cnt = dense ? Tb : min(max(cnt, 0), k_row);
   const int32_t* __restrict__ list = blk_idx + row_id * k_row;
+  const int U = cnt * C::KT;                            // units to process
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in a scalar register
@@ -91,28 +121,24 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
   const size_t head_off = (size_t)bh * Tb * BLK * D;    // elements; same for qp, kp, vp, op
   const unsigned char* __restrict__ kbase = reinterpret_cast<const unsigned char*>(kp + head_off);
   const unsigned char* __restrict__ vbase = reinterpret_cast<const unsigned char*>(vp + head_off);
-  const uint32_t k_lane = (uint32_t)((lh * BLK + wc * C::KH + l32) * 16);          // LDS byte offsets of this lane's
-  const uint32_t v_lane = (uint32_t)(((2 * wc * C::KS + lh) * D + l32) * 16);      // first K / V^T operand chunk
+  // LDS byte offsets of this lane's first operand chunk inside a K part / a V^T part
+  const uint32_t k_lane = (uint32_t)((lh * 64 + wc * 32 + l32) * 16);
+  const uint32_t v_lane = (uint32_t)(((wc * 4 + lh) * D + l32) * 16);
   auto block_at = [&](int it) {
     const int j = dense ? it : list[it];
     return min(max(j, 0), Tb - 1);                      // a corrupt list can give wrong results, never a fault
   };
+  // global byte offset of unit x's part inside kp / vp of this head (x clamped: loads past the
+  // end re-fetch the last unit into a free slot, which keeps the outstanding-load count uniform)
+  auto unit_off = [&](int x) {
+    x = min(x, U - 1);
+    return (size_t)block_at(x / C::KT) * C::TILE_BYTES + (size_t)(x % C::KT) * C::UNIT_BYTES;
+  };
+  // Only the last listed block can be the ragged last block of the sequence (lists ascend).
+  int partial_begin = U;
+  if (U > 0 && last_valid < BLK && block_at(cnt - 1) == Tb - 1) partial_begin = (cnt - 1) * C::KT;
 
-  if (cnt > 0) {
-    const size_t off = (size_t)block_at(0) * C::TILE_BYTES;
-    dma_tile<C::NW, C::DMA>(KsA, kbase + off, wave, tid16);
-    dma_tile<C::NW, C::DMA>(VsA, vbase + off, wave, tid16);
-  }
-
-  // ---- Q fragments (B operand of S^T), resident for the whole kernel -----------------
   bf16x8 qf[C::QT][C::DS];
-#pragma unroll
-  for (int qt = 0; qt < C::QT; ++qt) {
-    const __bf16* qrow = qp + head_off + ((size_t)qi * BLK + 64 * wa + 32 * qt + l32) * D + 8 * lh;
-#pragma unroll
-    for (int s = 0; s < C::DS; ++s) qf[qt][s] = *reinterpret_cast<const bf16x8*>(qrow + 16 * s);
-  }
-
   f32x16 o[C::DT][C::QT];
 #pragma unroll
   for (int dt = 0; dt < C::DT; ++dt)
@@ -124,111 +150,208 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
 #pragma unroll
   for (int qt = 0; qt < C::QT; ++qt) { m_run[qt] = -INFINITY; l_run[qt] = 0.f; }
 
-  // One K/V block: wait for its tiles, start the loads of the next block into the other
-  // buffers, then S^T, softmax, O^T.
-  auto step = [&](const unsigned char* Kc, const unsigned char* Vc, unsigned char* Kn, unsigned char* Vn, int it) {
-    const int j = block_at(it);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();     // tiles of block `it` are complete; nobody still reads the other buffers
-    if (it + 1 < cnt) {
-      const size_t off = (size_t)block_at(it + 1) * C::TILE_BYTES;
-      dma_tile<C::NW, C::DMA>(Kn, kbase + off, wave, tid16);
-      dma_tile<C::NW, C::DMA>(Vn, vbase + off, wave, tid16);
-    }
-
-    // ---- S^T = K Q^T (eq. 1, unscaled) ----------------------------------------------------
-    f32x16 s[C::KT][C::QT];
+  // ---- building blocks ------------------------------------------------------------------
+  // S^T of one unit (eq. 1, unscaled): 32 keys x 64 queries.
+  auto qk = [&](const unsigned char* Kb, f32x16 (&S)[C::QT]) {
 #pragma unroll
-    for (int kt = 0; kt < C::KT; ++kt) {
+    for (int qt = 0; qt < C::QT; ++qt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[qt][i] = 0.f;
+#pragma unroll
+    for (int ds = 0; ds < C::DS; ++ds) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Kb + k_lane + ds * 2048);   // chunk 2*ds + lh, row wc*32 + l32
 #pragma unroll
       for (int qt = 0; qt < C::QT; ++qt)
+        S[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qt][ds], S[qt], 0, 0, 0);
+    }
+  };
+  // O^T += V^T P^T for one unit (eq. 4).
+  auto pv = [&](const unsigned char* Vb, const bf16x8 (&P)[C::QT][2]) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[kt][qt][i] = 0.f;
+    for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-      for (int ds = 0; ds < C::DS; ++ds) {
-        // chunk 2*ds + lh of key row wc*KH + 32*kt + l32
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(Kc + k_lane + (2 * ds * BLK + 32 * kt) * 16);
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vb + v_lane + (2 * ks * D + 32 * dt) * 16);
 #pragma unroll
         for (int qt = 0; qt < C::QT; ++qt)
-          s[kt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qt][ds], s[kt][qt], 0, 0, 0);
+          o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, P[qt][ks], o[dt][qt], 0, 0, 0);
       }
-    }
-    // keys past the end of the sequence exist only in the last block
-    if (j == Tb - 1 && last_valid < BLK) {
+  };
+  // The same two products with the A operands fetched from LDS ahead of time, so that the
+  // LDS latency is paid once per step (under the row-maximum arithmetic), not per MFMA.
+  auto load_k = [&](const unsigned char* Kb, bf16x8 (&A)[C::DS]) {
 #pragma unroll
-      for (int kt = 0; kt < C::KT; ++kt)
+    for (int ds = 0; ds < C::DS; ++ds) A[ds] = *reinterpret_cast<const bf16x8*>(Kb + k_lane + ds * 2048);
+  };
+  auto load_v = [&](const unsigned char* Vb, bf16x8 (&A)[C::DT][2]) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = wc * C::KH + 32 * kt + 8 * (i / 4) + 4 * lh + (i % 4);
-          if (key >= last_valid) {
+    for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
-            for (int qt = 0; qt < C::QT; ++qt) s[kt][qt][i] = -INFINITY;
-          }
-        }
-    }
-
-    // ---- online softmax (eqs. 2, 3), one query column per lane ---------------------------
-    // The running maximum is only raised when a block exceeds it by more than 2^8: until
-    // then probabilities are at most 256 (exact final normalisation makes the reference
-    // point irrelevant), and the 128-register output rescale is skipped for most blocks.
-    bf16x8 pf[C::QT][C::KS];
+      for (int ks = 0; ks < 2; ++ks)
+        A[dt][ks] = *reinterpret_cast<const bf16x8*>(Vb + v_lane + (2 * ks * D + 32 * dt) * 16);
+  };
+  auto qk_r = [&](const bf16x8 (&A)[C::DS], f32x16 (&S)[C::QT]) {
+#pragma unroll
+    for (int qt = 0; qt < C::QT; ++qt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[qt][i] = 0.f;
+#pragma unroll
+    for (int ds = 0; ds < C::DS; ++ds)
+#pragma unroll
+      for (int qt = 0; qt < C::QT; ++qt)
+        S[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[ds], qf[qt][ds], S[qt], 0, 0, 0);
+  };
+  auto pv_r = [&](const bf16x8 (&A)[C::DT][2], const bf16x8 (&P)[C::QT][2]) {
+#pragma unroll
+    for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int qt = 0; qt < C::QT; ++qt)
+          o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[dt][ks], P[qt][ks], o[dt][qt], 0, 0, 0);
+  };
+  // scaled row maxima of one unit, per query column (both lane halves end up with the same value)
+  auto rowmax = [&](const f32x16 (&S)[C::QT], float (&mx)[C::QT]) {
 #pragma unroll
     for (int qt = 0; qt < C::QT; ++qt) {
-      float mx = -INFINITY;
+      float v = S[qt][0];
 #pragma unroll
-      for (int kt = 0; kt < C::KT; ++kt)
+      for (int i = 1; i < 16; ++i) v = fmaxf(v, S[qt][i]);
+      // exchange with lane l^32 on the vector ALU (an LDS shuffle would have to wait for the operand reads in flight)
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+      mx[qt] = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * scale_log2;
+    }
+  };
+  // Rarely taken: raise the running maximum (eq. 2) and rescale sum and output (eqs. 3, 4);
+  // also where keys past the end of the sequence are masked out.
+  // The maximum is only raised when a unit exceeds it by more than 2^8: until then
+  // probabilities are at most 256 (the exact final normalisation makes the reference point
+  // irrelevant) and the 128-register output rescale is skipped for most units.
+  auto slow_path = [&](f32x16 (&S)[C::QT], float (&mx)[C::QT], int s) {
+    if (s >= partial_begin) {
+      const int kt = s % C::KT;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kt][qt][i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
-      const bool raise = mx > m_run[qt] + 8.0f;           // -inf + 8 = -inf: the first finite block always raises
+      for (int i = 0; i < 16; ++i) {
+        const int key = wc * C::KH + 32 * kt + 8 * (i / 4) + 4 * lh + (i % 4);
+        if (key >= last_valid) {
+#pragma unroll
+          for (int qt = 0; qt < C::QT; ++qt) S[qt][i] = -INFINITY;
+        }
+      }
+      rowmax(S, mx);
+    }
+#pragma unroll
+    for (int qt = 0; qt < C::QT; ++qt) {
+      const bool raise = mx[qt] > m_run[qt] + 8.0f;       // -inf + 8 = -inf: the first finite unit always raises
       if (__builtin_amdgcn_ballot_w64(raise) != 0ull) {
-        const float m_new = raise ? mx : m_run[qt];
-        const float alpha = raise ? __builtin_amdgcn_exp2f(m_run[qt] - m_new) : 1.0f;   // exp2(-inf) = 0
-        m_run[qt] = m_new;
+        const float alpha = raise ? __builtin_amdgcn_exp2f(m_run[qt] - mx[qt]) : 1.0f;   // exp2(-inf) = 0
+        m_run[qt] = raise ? mx[qt] : m_run[qt];
         l_run[qt] *= alpha;
 #pragma unroll
         for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
           for (int i = 0; i < 16; ++i) o[dt][qt][i] *= alpha;
       }
+    }
+  };
+  auto need_slow = [&](const float (&mx)[C::QT], int s) {
+    bool raise = false;
+#pragma unroll
+    for (int qt = 0; qt < C::QT; ++qt) raise |= mx[qt] > m_run[qt] + 8.0f;
+    return (__builtin_amdgcn_ballot_w64(raise) != 0ull) || (s >= partial_begin);
+  };
+  // probabilities of one unit relative to the running maximum, packed as B operands (eqs. 2, 3)
+  auto expsum = [&](const f32x16 (&S)[C::QT], bf16x8 (&P)[C::QT][2]) {
+#pragma unroll
+    for (int qt = 0; qt < C::QT; ++qt) {
       const float m_use = (m_run[qt] == -INFINITY) ? 0.f : m_run[qt];
       float rs = 0.f;
 #pragma unroll
-      for (int kt = 0; kt < C::KT; ++kt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][qt][i], scale_log2, -m_use));
-          s[kt][qt][i] = p;
-          rs += p;
-        }
-      l_run[qt] += rs;
-#pragma unroll
-      for (int ks = 0; ks < C::KS; ++ks)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pf[qt][ks][e] = (__bf16)s[ks / 2][qt][8 * (ks % 2) + e];
-    }
-
-    // ---- O^T += V^T P^T (eq. 4) ---------------------------------------------------------
-#pragma unroll
-    for (int dt = 0; dt < C::DT; ++dt) {
-#pragma unroll
-      for (int ks = 0; ks < C::KS; ++ks) {
-        // key chunk 2*(wc*KS + ks) + lh of channel row 32*dt + l32
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vc + v_lane + (2 * ks * D + 32 * dt) * 16);
-#pragma unroll
-        for (int qt = 0; qt < C::QT; ++qt)
-          o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[qt][ks], o[dt][qt], 0, 0, 0);
+      for (int i = 0; i < 16; ++i) {
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(S[qt][i], scale_log2, -m_use));
+        rs += p;
+        P[qt][i / 8][i % 8] = (__bf16)p;
       }
+      l_run[qt] += rs;
     }
   };
 
-  for (int it = 0; it < cnt; it += 2) {
-    step(KsA, VsA, KsB, VsB, it);
-    if (it + 1 < cnt) step(KsB, VsB, KsA, VsA, it + 1);
+  if (U > 0) {
+    // ---- prologue: fill the rings, load Q, first unit ------------------------------------
+    dma_unit<C::NW, C::LPW>(K0, kbase + unit_off(0), wave, tid16);
+    dma_unit<C::NW, C::LPW>(V0, vbase + unit_off(0), wave, tid16);
+    dma_unit<C::NW, C::LPW>(K1, kbase + unit_off(1), wave, tid16);
+    dma_unit<C::NW, C::LPW>(K2, kbase + unit_off(2), wave, tid16);
+    dma_unit<C::NW, C::LPW>(K3, kbase + unit_off(3), wave, tid16);
+    dma_unit<C::NW, C::LPW>(V1, vbase + unit_off(1), wave, tid16);
+#pragma unroll
+    for (int qt = 0; qt < C::QT; ++qt) {
+      const __bf16* qrow = qp + head_off + ((size_t)qi * BLK + 64 * wa + 32 * qt + l32) * D + 8 * lh;
+#pragma unroll
+      for (int ds = 0; ds < C::DS; ++ds) qf[qt][ds] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ds);
+    }
+    f32x16 Sa[C::QT], Sb[C::QT];
+    bf16x8 Pa[C::QT][2], Pb[C::QT][2];
+    float mx[C::QT];
+    bf16x8 ak[C::DS], av[C::DT][2];
+    ring_barrier<0>();
+    qk(K0, Sa);                                           // S_0
+    __syncthreads();                                      // everyone is done with slot K0
+    // step 0 (no P yet): softmax of unit 0 around S_1
+    dma_unit<C::NW, C::LPW>(K0, kbase + unit_off(4), wave, tid16);
+    dma_unit<C::NW, C::LPW>(V2, vbase + unit_off(2), wave, tid16);
+    rowmax(Sa, mx);
+    slow_path(Sa, mx, 0);
+    expsum(Sa, Pa);
+    qk(K1, Sb);
+
+    // ---- steady state: step s = products S_{s+1} and V P_{s-1} around the softmax of unit s --
+    // Ring slots: K part of unit x and V^T part of unit x live in slot x % 4.  Step s loads the
+    // K part of unit s+4 and the V^T part of unit s+2 into the slots freed by step s-1.
+#define RF2_STEP(s_, Kissue, Vissue, Vprev, Knext, Scur, Snext, Pprev, Pcur)                 \
+  {                                                                                          \
+    ring_barrier<C::PENDING>();                                                              \
+    dma_unit<C::NW, C::LPW>(Kissue, kbase + off_k, wave, tid16);                             \
+    dma_unit<C::NW, C::LPW>(Vissue, vbase + off_v, wave, tid16);                             \
+    off_k = unit_off((s_) + 5); /* for the next step: the list entry is fetched a step ahead */ \
+    off_v = unit_off((s_) + 3);                                                              \
+    load_v(Vprev, av);                                                                       \
+    load_k(Knext, ak);                                                                       \
+    rowmax(Scur, mx);                                                                        \
+    if (need_slow(mx, (s_))) {                                                               \
+      /* the pending product must reach O before O is rescaled; it is then neutralised */    \
+      pv_r(av, Pprev);                                                                       \
+      _Pragma("unroll") for (int qt = 0; qt < C::QT; ++qt)                                   \
+        _Pragma("unroll") for (int ks = 0; ks < 2; ++ks)                                     \
+          _Pragma("unroll") for (int e = 0; e < 8; ++e) Pprev[qt][ks][e] = (__bf16)0.f;      \
+      slow_path(Scur, mx, (s_));                                                             \
+    }                                                                                        \
+    pv_r(av, Pprev);                                                                         \
+    expsum(Scur, Pcur);                                                                      \
+    qk_r(ak, Snext);                                                                         \
+  }
+    size_t off_k = unit_off(5), off_v = unit_off(3);
+    for (int s = 1; s < U; s += 4) {
+      RF2_STEP(s, K1, V3, V0, K2, Sb, Sa, Pa, Pb)
+      if (s + 1 < U) RF2_STEP(s + 1, K2, V0, V1, K3, Sa, Sb, Pb, Pa)
+      if (s + 2 < U) RF2_STEP(s + 2, K3, V1, V2, K0, Sb, Sa, Pa, Pb)
+      if (s + 3 < U) RF2_STEP(s + 3, K0, V2, V3, K1, Sa, Sb, Pb, Pa)
+    }
+#undef RF2_STEP
+    // ---- last product: O += V P_{U-1} ------------------------------------------------------
+    ring_barrier<0>();
+    switch ((U - 1) & 3) {
+      case 0: pv(V0, Pa); break;
+      case 1: pv(V1, Pb); break;
+      case 2: pv(V2, Pa); break;
+      default: pv(V3, Pb); break;
+    }
   }
 
   // ---- merge the two key halves and write the Q block -------------------------------------
-  __syncthreads();                                        // every wavefront is done with the tiles
+  __syncthreads();                                        // every wavefront is done with the rings
+  float* ml = reinterpret_cast<float*>(V0);               // [wa][wc][qt][m|l][lane]: 4 KiB at most
+  static_assert((BLK / 64) * 2 * C::QT * 2 * 64 * 4 <= C::UNIT_BYTES, "");
   float l_tot[C::QT];
 #pragma unroll
   for (int qt = 0; qt < C::QT; ++qt) {
@@ -247,16 +370,17 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     const float w_mine = __builtin_amdgcn_exp2f(m_run[qt] - m_ref), w_o = __builtin_amdgcn_exp2f(m_o - m_ref);
     m_all[qt] = m;
     l_all[qt] = l_tot[qt] * w_mine + l_o * w_o;
-    f_mine[qt] = w_mine / l_all[qt];
+    f_mine[qt] = l_all[qt] > 0.f ? w_mine / l_all[qt] : 0.f;   // a row with no kept key yields zeros
   }
-  // The c=1 wavefront of each query half hands its scaled partial output to the c=0 one.
-  // The exchange area is the (now idle) pair of K buffers, in 8 KiB units of one (wa, dt) each.
-  constexpr int UNIT_FLOATS = C::QT * 16 * 64;
-  constexpr int UPB = C::TILE_BYTES / (UNIT_FLOATS * 4);     // units per buffer
-  static_assert(UPB >= 1 && (BLK / 64) * C::DT <= 2 * UPB, "exchange area must fit the two K buffers");
-  auto unit = [&](int dt) -> float* {
-    const int u = wa * C::DT + dt;
-    return reinterpret_cast<float*>(u < UPB ? KsA : KsB) + (u % UPB) * UNIT_FLOATS;
+  // The c=1 wavefront of each query half hands its scaled partial output to the c=0 one through
+  // the (now idle) K ring, in 8 KiB units of one (wa, dt) each.
+  constexpr int XU_FLOATS = C::QT * 16 * 64;
+  constexpr int UPB = C::UNIT_BYTES / (XU_FLOATS * 4);    // exchange units per ring slot
+  static_assert(UPB >= 1 && (BLK / 64) * C::DT <= 4 * UPB, "exchange area must fit the K ring");
+  auto xunit = [&](int dt) -> float* {
+    const int u = wa * C::DT + dt, b = u / UPB;
+    unsigned char* base = b == 0 ? K0 : b == 1 ? K1 : b == 2 ? K2 : K3;
+    return reinterpret_cast<float*>(base) + (u % UPB) * XU_FLOATS;
   };
   if (wc == 1) {
 #pragma unroll
@@ -264,8 +388,7 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
 #pragma unroll
       for (int qt = 0; qt < C::QT; ++qt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-          unit(dt)[(qt * 16 + i) * 64 + lane] = o[dt][qt][i] * f_mine[qt];
+        for (int i = 0; i < 16; ++i) xunit(dt)[(qt * 16 + i) * 64 + lane] = o[dt][qt][i] * f_mine[qt];
   }
   __syncthreads();
   if (wc == 0) {
@@ -281,7 +404,7 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int i = 4 * g + e;
-            const float other = unit(dt)[(qt * 16 + i) * 64 + lane];
+            const float other = xunit(dt)[(qt * 16 + i) * 64 + lane];
             pk[e] = (__bf16)(o[dt][qt][i] * f_mine[qt] + other);
           }
           *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g + 4 * lh) = pk;

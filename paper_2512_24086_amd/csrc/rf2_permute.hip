@@ -13,9 +13,10 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 
 // One workgroup gathers one block of BLK permuted rows of Q (blockIdx.z = 0) or K (1),
 // writes them in permuted order and reduces their column sums to the block mean.
-// Q rows stay row-major; a K block is written as an operand tile [D/8][BLK][8]: the
-// 16-byte chunk c of row r lands at chunk slot c*BLK + r, the order in which the attention
-// kernel's matrix-core operand reads walk it.
+// Q rows stay row-major; a K block is written as BLK/64 operand parts [D/8][64][8]: with
+// KH = BLK/2, the 16-byte chunk c of block row r lands in part (r % KH) / 32 at chunk slot
+// c*64 + (r / KH)*32 + r % 32 -- the order in which the attention kernel's matrix-core
+// operand reads walk it (a part holds one 32-key tile of each key half).
 template <int D, int BLK>
 __global__ void __launch_bounds__(256) permute_pool_kernel(
     const uint4* __restrict__ q, const uint4* __restrict__ k, uint4* __restrict__ qp, uint4* __restrict__ kp,
@@ -36,7 +37,9 @@ __global__ void __launch_bounds__(256) permute_pool_kernel(
     const int n = perm[blk * BLK + r];
     uint4 x = make_uint4(0u, 0u, 0u, 0u);
     if (n >= 0) x = src[(size_t)n * CH + c];
-    dst[blockIdx.z == 0 ? r * CH + c : c * BLK + r] = x;
+    constexpr int KH = BLK / 2;
+    const int kslot = ((r % KH) / 32 * CH + c) * 64 + (r / KH) * 32 + r % 32;
+    dst[blockIdx.z == 0 ? r * CH + c : kslot] = x;
     acc[0] += bf16_lo(x.x); acc[1] += bf16_hi(x.x);
     acc[2] += bf16_lo(x.y); acc[3] += bf16_hi(x.y);
     acc[4] += bf16_lo(x.z); acc[5] += bf16_hi(x.z);
@@ -60,9 +63,11 @@ __global__ void __launch_bounds__(256) permute_pool_kernel(
 __device__ __forceinline__ int rho(int r) { return (r & 3) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
 // One workgroup gathers one block of BLK permuted rows of V into LDS and writes the
-// block as the operand tile [BLK/8][D][8] of the attention kernel's second product:
-// 16-byte chunk (g, ch) holds channel ch of 8 keys of the block, chunks 2G and 2G+1
-// covering the 16-key group G in the order 0-3, 8-11 | 4-7, 12-15.
+// block as BLK/64 operand parts [8][D][8] of the attention kernel's second product.
+// Storage position s of a key inside its block: each 16-key group is listed in the order
+// 0-3, 8-11, 4-7, 12-15.  With KH = BLK/2, position s goes to part (s % KH) / 32, chunk
+// g = (s / KH)*4 + (s % 32) / 8, element s % 8; the 16-byte chunk (part, g, ch) holds
+// channel ch of those 8 keys.
 template <int D, int BLK>
 __global__ void __launch_bounds__(256) permute_vtile_kernel(
     const uint4* __restrict__ v, uint4* __restrict__ vp, const int32_t* __restrict__ perm, int N, int n_blocks) {
@@ -82,13 +87,16 @@ __global__ void __launch_bounds__(256) permute_vtile_kernel(
   }
   __syncthreads();
   constexpr int OC = BLK / 8;        // key chunks per block
+  constexpr int KH = BLK / 2;
   uint4* __restrict__ dst = vp + ((size_t)bh * n_blocks + blk) * D * OC;
   for (int o = threadIdx.x; o < D * OC; o += 256) {
-    const int g = o / D, ch = o % D;   // consecutive lanes -> consecutive channels: contiguous 16-byte stores
+    const int pg = o / D, ch = o % D;  // consecutive lanes -> consecutive channels: contiguous 16-byte stores
+    const int part = pg / 8, g = pg % 8;
+    const int sbase = (g / 4) * KH + part * 32 + (g % 4) * 8;   // first storage position of this chunk
     uint32_t w[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int s0 = 8 * g + 2 * e, s1 = s0 + 1;
+      const int s0 = sbase + 2 * e, s1 = s0 + 1;
       const int k0 = (s0 & ~15) + rho(s0 & 15), k1 = (s1 & ~15) + rho(s1 & 15);
       w[e] = (uint32_t)tile[k0 * PITCH + ch] | ((uint32_t)tile[k1 * PITCH + ch] << 16);
     }

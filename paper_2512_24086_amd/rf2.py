@@ -125,8 +125,8 @@ class Plan:
         bf = dict(dtype=torch.bfloat16, device=device)
         buf = dict(
             qp=torch.empty(*bh, i.N_pad, c.head_dim, **bf),
-            kp=torch.empty(*bh, i.n_blocks, c.head_dim // 8, c.block, 8, **bf),
-            vp=torch.empty(*bh, i.n_blocks, c.block // 8, c.head_dim, 8, **bf),
+            kp=torch.empty(*bh, i.n_blocks, c.block // 64, c.head_dim // 8, 64, 8, **bf),
+            vp=torch.empty(*bh, i.n_blocks, c.block // 64, 8, c.head_dim, 8, **bf),
             qbar=torch.empty(*bh, i.n_blocks, c.head_dim, dtype=torch.float32, device=device),
             kbar=torch.empty(*bh, i.n_blocks, c.head_dim, dtype=torch.float32, device=device),
             blk_idx=torch.empty(*bh, i.n_blocks, i.k_row, dtype=torch.int32, device=device),

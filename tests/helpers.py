@@ -22,20 +22,25 @@ def rho(r):
 
 
 def kp_to_rows(kp: np.ndarray) -> np.ndarray:
-    """Decode the K operand tiles [Tb, d/8, b, 8] of one head into row-major [Tb*b, d]."""
-    Tb, C, b, _ = kp.shape
-    return np.transpose(kp, (0, 2, 1, 3)).reshape(Tb * b, C * 8)
+    """Decode the K operand tiles [Tb, b/64, d/8, 64, 8] of one head into row-major [Tb*b, d]."""
+    Tb, parts, C, _, _ = kp.shape
+    b, KH = parts * 64, parts * 32
+    r = np.arange(b)
+    part, slot = (r % KH) // 32, (r // KH) * 32 + r % 32
+    rows = kp[:, part, :, slot, :]                     # [b, Tb, C, 8]
+    return np.transpose(rows, (1, 0, 2, 3)).reshape(Tb * b, C * 8)
 
 
 def vp_to_rows(vp: np.ndarray) -> np.ndarray:
-    """Decode the V operand tiles [Tb, b/8, d, 8] of one head into row-major [Tb*b, d]."""
-    Tb, G, d, _ = vp.shape
-    b = G * 8
-    s = np.arange(b)                                  # storage position inside the block: chunk g = s//8, e = s%8
+    """Decode the V operand tiles [Tb, b/64, 8, d, 8] of one head into row-major [Tb*b, d]."""
+    Tb, parts, _, d, _ = vp.shape
+    b, KH = parts * 64, parts * 32
+    s = np.arange(b)                                  # storage position inside the block
     key_of_pos = (s & ~15) + rho(s & 15)
-    by_pos = np.transpose(vp, (0, 1, 3, 2)).reshape(Tb, b, d)      # [Tb, position, channel]
-    out = np.empty_like(by_pos)
-    out[:, key_of_pos, :] = by_pos
+    part, g, e = (s % KH) // 32, (s // KH) * 4 + (s % 32) // 8, s % 8
+    by_pos = vp[:, part, g, :, e]                      # [b, Tb, d]
+    out = np.empty((Tb, b, d), dtype=vp.dtype)
+    out[:, key_of_pos, :] = np.transpose(by_pos, (1, 0, 2))
     return out.reshape(Tb * b, d)
 
 
