@@ -70,6 +70,16 @@ __device__ __forceinline__ void dma_unit(unsigned char* lds, const unsigned char
   }
 }
 
+template <int NW>
+__device__ __forceinline__ void dma_one(unsigned char* lds, const unsigned char* g, int u, int wave, uint32_t tid16) {
+  const uint32_t m0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds +
+                      (uint32_t)((u * NW + wave) * 1024);
+  const unsigned char* src = g + u * (NW * 1024) + tid16;
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m0), "v"(src) : "memory");
+}
+
+__device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // Workgroup barrier of the steady-state loop: waits until at most N of this wavefront's
 // direct-to-LDS loads are still in flight, then s_barrier.  __syncthreads() cannot be used
 // there: its release fence would wait for ALL outstanding loads, i.e. also for the parts
@@ -90,16 +100,10 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     float* __restrict__ lse, const int32_t* __restrict__ row_order, int rows_per_xcd, int Tb, int k_row,
     int last_valid, float scale_log2) {
   using C = AttnCfg<D, BLK>;
-  // Rings of 4 K parts and 4 V^T parts.
+  // Rings of 4 K parts (slots 0-3) and 4 V^T parts (slots 4-7); unit x uses slot x % 4 of each.
   __shared__ __attribute__((aligned(1024))) unsigned char ring[8 * C::UNIT_BYTES];
-  unsigned char* const K0 = ring;
-  unsigned char* const K1 = ring + 1 * C::UNIT_BYTES;
-  unsigned char* const K2 = ring + 2 * C::UNIT_BYTES;
-  unsigned char* const K3 = ring + 3 * C::UNIT_BYTES;
-  unsigned char* const V0 = ring + 4 * C::UNIT_BYTES;
-  unsigned char* const V1 = ring + 5 * C::UNIT_BYTES;
-  unsigned char* const V2 = ring + 6 * C::UNIT_BYTES;
-  unsigned char* const V3 = ring + 7 * C::UNIT_BYTES;
+  unsigned char* const kring = ring;
+  unsigned char* const vring = ring + 4 * C::UNIT_BYTES;
 
   // ---- which Q block ---------------------------------------------------------------
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -151,64 +155,17 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
   for (int qt = 0; qt < C::QT; ++qt) { m_run[qt] = -INFINITY; l_run[qt] = 0.f; }
 
   // ---- building blocks ------------------------------------------------------------------
-  // S^T of one unit (eq. 1, unscaled): 32 keys x 64 queries.
-  auto qk = [&](const unsigned char* Kb, f32x16 (&S)[C::QT]) {
-#pragma unroll
-    for (int qt = 0; qt < C::QT; ++qt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) S[qt][i] = 0.f;
-#pragma unroll
-    for (int ds = 0; ds < C::DS; ++ds) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(Kb + k_lane + ds * 2048);   // chunk 2*ds + lh, row wc*32 + l32
-#pragma unroll
-      for (int qt = 0; qt < C::QT; ++qt)
-        S[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qt][ds], S[qt], 0, 0, 0);
-    }
-  };
-  // O^T += V^T P^T for one unit (eq. 4).
-  auto pv = [&](const unsigned char* Vb, const bf16x8 (&P)[C::QT][2]) {
-#pragma unroll
-    for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vb + v_lane + (2 * ks * D + 32 * dt) * 16);
-#pragma unroll
-        for (int qt = 0; qt < C::QT; ++qt)
-          o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, P[qt][ks], o[dt][qt], 0, 0, 0);
-      }
-  };
-  // The same two products with the A operands fetched from LDS ahead of time, so that the
-  // LDS latency is paid once per step (under the row-maximum arithmetic), not per MFMA.
-  auto load_k = [&](const unsigned char* Kb, bf16x8 (&A)[C::DS]) {
-#pragma unroll
-    for (int ds = 0; ds < C::DS; ++ds) A[ds] = *reinterpret_cast<const bf16x8*>(Kb + k_lane + ds * 2048);
-  };
-  auto load_v = [&](const unsigned char* Vb, bf16x8 (&A)[C::DT][2]) {
-#pragma unroll
-    for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
-        A[dt][ks] = *reinterpret_cast<const bf16x8*>(Vb + v_lane + (2 * ks * D + 32 * dt) * 16);
-  };
-  auto qk_r = [&](const bf16x8 (&A)[C::DS], f32x16 (&S)[C::QT]) {
-#pragma unroll
-    for (int qt = 0; qt < C::QT; ++qt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) S[qt][i] = 0.f;
-#pragma unroll
-    for (int ds = 0; ds < C::DS; ++ds)
-#pragma unroll
-      for (int qt = 0; qt < C::QT; ++qt)
-        S[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[ds], qf[qt][ds], S[qt], 0, 0, 0);
-  };
-  auto pv_r = [&](const bf16x8 (&A)[C::DT][2], const bf16x8 (&P)[C::QT][2]) {
-#pragma unroll
-    for (int dt = 0; dt < C::DT; ++dt)
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-        for (int qt = 0; qt < C::QT; ++qt)
-          o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[dt][ks], P[qt][ks], o[dt][qt], 0, 0, 0);
+  // One step has NQ + NP "slots" of two MFMAs each (one A operand from LDS, two query tiles):
+  // slots 0..NQ-1 are the k-steps of S^T_{s+1} = K Q^T (eq. 1, unscaled), slots NQ.. are the
+  // (channel tile, k-step) pairs of O^T += V^T P^T_{s-1} (eq. 4).
+  constexpr int NQ = C::DS, NP = C::DT * 2, NSLOT = NQ + NP;
+  constexpr int PD = 4;                                  // operand reads run this many slots ahead
+  constexpr int EPS = 32 / NSLOT;                        // softmax elements handled per slot
+  static_assert(32 % NSLOT == 0 && 2 * C::LPW <= NSLOT, "slot plan");
+  auto operand = [&](uint32_t k_addr, uint32_t v_addr, int g) -> bf16x8 {
+    if (g < NQ) return *reinterpret_cast<const bf16x8*>(ring + k_addr + g * 2048);   // chunk 2g+lh, row wc*32+l32
+    const int dt = (g - NQ) / 2, ks = (g - NQ) % 2;      // key chunk wc*4 + 2ks + lh, channel 32dt + l32
+    return *reinterpret_cast<const bf16x8*>(ring + v_addr + (2 * ks * D + 32 * dt) * 16);
   };
   // scaled row maxima of one unit, per query column (both lane halves end up with the same value)
   auto rowmax = [&](const f32x16 (&S)[C::QT], float (&mx)[C::QT]) {
@@ -217,17 +174,37 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
       float v = S[qt][0];
 #pragma unroll
       for (int i = 1; i < 16; ++i) v = fmaxf(v, S[qt][i]);
-      // exchange with lane l^32 on the vector ALU (an LDS shuffle would have to wait for the operand reads in flight)
+      // exchange with lane l^32 on the vector ALU (an LDS shuffle would wait for operand reads in flight)
       const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
       mx[qt] = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * scale_log2;
     }
   };
-  // Rarely taken: raise the running maximum (eq. 2) and rescale sum and output (eqs. 3, 4);
-  // also where keys past the end of the sequence are masked out.
-  // The maximum is only raised when a unit exceeds it by more than 2^8: until then
-  // probabilities are at most 256 (the exact final normalisation makes the reference point
-  // irrelevant) and the 128-register output rescale is skipped for most units.
-  auto slow_path = [&](f32x16 (&S)[C::QT], float (&mx)[C::QT], int s) {
+  // The running maximum (eq. 2) is only raised when a unit exceeds it by more than 2^8: until
+  // then probabilities are at most 256 (the exact final normalisation makes the reference point
+  // irrelevant) and the 128-register output rescale of eqs. 3, 4 is skipped for most units.
+  auto need_slow = [&](const float (&mx)[C::QT], int s) {
+    bool raise = false;
+#pragma unroll
+    for (int qt = 0; qt < C::QT; ++qt) raise |= mx[qt] > m_run[qt] + 8.0f;   // -inf + 8 = -inf: first unit raises
+    return (__builtin_amdgcn_ballot_w64(raise) != 0ull) || (s >= partial_begin);
+  };
+  // Rarely taken, before the step proper: the pending product V P_{s-1} must reach O before O
+  // is rescaled (it is then neutralised); keys past the end of the sequence are masked here.
+  auto slow_path = [&](f32x16 (&S)[C::QT], float (&mx)[C::QT], bf16x8 (&Pprev)[C::QT][2], uint32_t v_addr, int s) {
+#pragma unroll
+    for (int g = NQ; g < NSLOT; ++g) {
+      const bf16x8 a = operand(0, v_addr, g);
+      const int dt = (g - NQ) / 2, ks = (g - NQ) % 2;
+#pragma unroll
+      for (int qt = 0; qt < C::QT; ++qt)
+        o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Pprev[qt][ks], o[dt][qt], 0, 0, 0);
+    }
+#pragma unroll
+    for (int qt = 0; qt < C::QT; ++qt)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) Pprev[qt][ks][e] = (__bf16)0.f;
     if (s >= partial_begin) {
       const int kt = s % C::KT;
 #pragma unroll
@@ -242,7 +219,7 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     }
 #pragma unroll
     for (int qt = 0; qt < C::QT; ++qt) {
-      const bool raise = mx[qt] > m_run[qt] + 8.0f;       // -inf + 8 = -inf: the first finite unit always raises
+      const bool raise = mx[qt] > m_run[qt] + 8.0f;
       if (__builtin_amdgcn_ballot_w64(raise) != 0ull) {
         const float alpha = raise ? __builtin_amdgcn_exp2f(m_run[qt] - mx[qt]) : 1.0f;   // exp2(-inf) = 0
         m_run[qt] = raise ? mx[qt] : m_run[qt];
@@ -254,36 +231,82 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
       }
     }
   };
-  auto need_slow = [&](const float (&mx)[C::QT], int s) {
-    bool raise = false;
-#pragma unroll
-    for (int qt = 0; qt < C::QT; ++qt) raise |= mx[qt] > m_run[qt] + 8.0f;
-    return (__builtin_amdgcn_ballot_w64(raise) != 0ull) || (s >= partial_begin);
-  };
-  // probabilities of one unit relative to the running maximum, packed as B operands (eqs. 2, 3)
-  auto expsum = [&](const f32x16 (&S)[C::QT], bf16x8 (&P)[C::QT][2]) {
+
+  size_t off_k = 0, off_v = 0;
+  bool slow = true;
+  // Step s: products S_{s+1} and V P_{s-1} around the softmax arithmetic of unit s (eqs. 2, 3),
+  // the loads of the K part of unit s+4 and the V^T part of unit s+2 spread between them, and
+  // the row maxima of unit s+1 at the end.  Unit x lives in slot x % 4 of its ring.
+  auto step = [&](int s, f32x16 (&Scur)[C::QT], f32x16 (&Snext)[C::QT], bf16x8 (&Pprev)[C::QT][2],
+                  bf16x8 (&Pcur)[C::QT][2], float (&mxcur)[C::QT], float (&mxnext)[C::QT]) {
+    ring_barrier<C::PENDING>();
+    const uint32_t k_addr = (uint32_t)(((s + 1) & 3) * C::UNIT_BYTES) + k_lane;                        // K part of unit s+1
+    const uint32_t v_addr = (uint32_t)((4 + ((s + 3) & 3)) * C::UNIT_BYTES) + v_lane;                  // V^T part of unit s-1
+    if (slow) slow_path(Scur, mxcur, Pprev, v_addr, s);
+    unsigned char* const k_dst = kring + (s & 3) * C::UNIT_BYTES;                                      // slot of unit s+4
+    unsigned char* const v_dst = vring + ((s + 2) & 3) * C::UNIT_BYTES;                                // slot of unit s+2
+    const unsigned char* const k_src = kbase + off_k;
+    const unsigned char* const v_src = vbase + off_v;
+    float m_use[C::QT], rs[C::QT];
 #pragma unroll
     for (int qt = 0; qt < C::QT; ++qt) {
-      const float m_use = (m_run[qt] == -INFINITY) ? 0.f : m_run[qt];
-      float rs = 0.f;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(S[qt][i], scale_log2, -m_use));
-        rs += p;
-        P[qt][i / 8][i % 8] = (__bf16)p;
-      }
-      l_run[qt] += rs;
+      m_use[qt] = (m_run[qt] == -INFINITY) ? 0.f : m_run[qt];
+      rs[qt] = 0.f;
     }
+    bf16x8 opnd[NSLOT];
+#pragma unroll
+    for (int g = 0; g < PD; ++g) opnd[g] = operand(k_addr, v_addr, g);
+#pragma unroll
+    for (int g = 0; g < NSLOT; ++g) {
+      if (g + PD < NSLOT) opnd[g + PD] = operand(k_addr, v_addr, g + PD);
+      if (g < NQ) {
+#pragma unroll
+        for (int qt = 0; qt < C::QT; ++qt) {
+          if (g == 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) Snext[qt][i] = 0.f;
+          }
+          Snext[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[g], qf[qt][g], Snext[qt], 0, 0, 0);
+        }
+      } else {
+        const int dt = (g - NQ) / 2, ks = (g - NQ) % 2;
+#pragma unroll
+        for (int qt = 0; qt < C::QT; ++qt)
+          o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[g], Pprev[qt][ks], o[dt][qt], 0, 0, 0);
+      }
+      // softmax arithmetic of unit s: EPS of the 32 values of this lane per slot
+#pragma unroll
+      for (int e = g * EPS; e < (g + 1) * EPS; ++e) {
+        const int qt = e / 16, i = e % 16;
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[qt][i], scale_log2, -m_use[qt]));
+        rs[qt] += p;
+        Pcur[qt][i / 8][i % 8] = (__bf16)p;
+      }
+      // one direct-to-LDS load per slot until both parts are on their way
+      if (g < C::LPW) dma_one<C::NW>(k_dst, k_src, g, wave, tid16);
+      else if (g < 2 * C::LPW) dma_one<C::NW>(v_dst, v_src, g - C::LPW, wave, tid16);
+    }
+    // Keep the softmax arithmetic inside this block (its results are only consumed by the next
+    // step, and the compiler would otherwise sink it there, out from under the MFMAs).
+#pragma unroll
+    for (int qt = 0; qt < C::QT; ++qt) {
+      asm volatile("" : "+v"(Pcur[qt][0]), "+v"(Pcur[qt][1]), "+v"(rs[qt]));
+      l_run[qt] += rs[qt];
+    }
+    rowmax(Snext, mxnext);
+    slow = need_slow(mxnext, s + 1);
+    off_k = unit_off(s + 5);      // list entries for the next step are fetched a step ahead
+    off_v = unit_off(s + 3);
   };
 
   if (U > 0) {
-    // ---- prologue: fill the rings, load Q, first unit ------------------------------------
-    dma_unit<C::NW, C::LPW>(K0, kbase + unit_off(0), wave, tid16);
-    dma_unit<C::NW, C::LPW>(V0, vbase + unit_off(0), wave, tid16);
-    dma_unit<C::NW, C::LPW>(K1, kbase + unit_off(1), wave, tid16);
-    dma_unit<C::NW, C::LPW>(K2, kbase + unit_off(2), wave, tid16);
-    dma_unit<C::NW, C::LPW>(K3, kbase + unit_off(3), wave, tid16);
-    dma_unit<C::NW, C::LPW>(V1, vbase + unit_off(1), wave, tid16);
+    // ---- prologue: fill the rings, load Q, S of unit 0 -------------------------------------
+    dma_unit<C::NW, C::LPW>(kring + 0 * C::UNIT_BYTES, kbase + unit_off(0), wave, tid16);
+    dma_unit<C::NW, C::LPW>(vring + 0 * C::UNIT_BYTES, vbase + unit_off(0), wave, tid16);
+    dma_unit<C::NW, C::LPW>(kring + 1 * C::UNIT_BYTES, kbase + unit_off(1), wave, tid16);
+    dma_unit<C::NW, C::LPW>(kring + 2 * C::UNIT_BYTES, kbase + unit_off(2), wave, tid16);
+    dma_unit<C::NW, C::LPW>(kring + 3 * C::UNIT_BYTES, kbase + unit_off(3), wave, tid16);
+    dma_unit<C::NW, C::LPW>(vring + 1 * C::UNIT_BYTES, vbase + unit_off(1), wave, tid16);
 #pragma unroll
     for (int qt = 0; qt < C::QT; ++qt) {
       const __bf16* qrow = qp + head_off + ((size_t)qi * BLK + 64 * wa + 32 * qt + l32) * D + 8 * lh;
@@ -292,70 +315,71 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     }
     f32x16 Sa[C::QT], Sb[C::QT];
     bf16x8 Pa[C::QT][2], Pb[C::QT][2];
-    float mx[C::QT];
-    bf16x8 ak[C::DS], av[C::DT][2];
+    float mxa[C::QT], mxb[C::QT];
     ring_barrier<0>();
-    qk(K0, Sa);                                           // S_0
-    __syncthreads();                                      // everyone is done with slot K0
-    // step 0 (no P yet): softmax of unit 0 around S_1
-    dma_unit<C::NW, C::LPW>(K0, kbase + unit_off(4), wave, tid16);
-    dma_unit<C::NW, C::LPW>(V2, vbase + unit_off(2), wave, tid16);
-    rowmax(Sa, mx);
-    slow_path(Sa, mx, 0);
-    expsum(Sa, Pa);
-    qk(K1, Sb);
-
-    // ---- steady state: step s = products S_{s+1} and V P_{s-1} around the softmax of unit s --
-    // Ring slots: K part of unit x and V^T part of unit x live in slot x % 4.  Step s loads the
-    // K part of unit s+4 and the V^T part of unit s+2 into the slots freed by step s-1.
-#define RF2_STEP(s_, Kissue, Vissue, Vprev, Knext, Scur, Snext, Pprev, Pcur)                 \
-  {                                                                                          \
-    ring_barrier<C::PENDING>();                                                              \
-    dma_unit<C::NW, C::LPW>(Kissue, kbase + off_k, wave, tid16);                             \
-    dma_unit<C::NW, C::LPW>(Vissue, vbase + off_v, wave, tid16);                             \
-    off_k = unit_off((s_) + 5); /* for the next step: the list entry is fetched a step ahead */ \
-    off_v = unit_off((s_) + 3);                                                              \
-    load_v(Vprev, av);                                                                       \
-    load_k(Knext, ak);                                                                       \
-    rowmax(Scur, mx);                                                                        \
-    if (need_slow(mx, (s_))) {                                                               \
-      /* the pending product must reach O before O is rescaled; it is then neutralised */    \
-      pv_r(av, Pprev);                                                                       \
-      _Pragma("unroll") for (int qt = 0; qt < C::QT; ++qt)                                   \
-        _Pragma("unroll") for (int ks = 0; ks < 2; ++ks)                                     \
-          _Pragma("unroll") for (int e = 0; e < 8; ++e) Pprev[qt][ks][e] = (__bf16)0.f;      \
-      slow_path(Scur, mx, (s_));                                                             \
-    }                                                                                        \
-    pv_r(av, Pprev);                                                                         \
-    expsum(Scur, Pcur);                                                                      \
-    qk_r(ak, Snext);                                                                         \
-  }
-    size_t off_k = unit_off(5), off_v = unit_off(3);
-    for (int s = 1; s < U; s += 4) {
-      RF2_STEP(s, K1, V3, V0, K2, Sb, Sa, Pa, Pb)
-      if (s + 1 < U) RF2_STEP(s + 1, K2, V0, V1, K3, Sa, Sb, Pb, Pa)
-      if (s + 2 < U) RF2_STEP(s + 2, K3, V1, V2, K0, Sb, Sa, Pa, Pb)
-      if (s + 3 < U) RF2_STEP(s + 3, K0, V2, V3, K1, Sa, Sb, Pb, Pa)
+#pragma unroll
+    for (int qt = 0; qt < C::QT; ++qt) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) Sa[qt][i] = 0.f;
+#pragma unroll
+      for (int ds = 0; ds < C::DS; ++ds)
+        Sa[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(k_lane, 0, ds), qf[qt][ds], Sa[qt], 0, 0, 0);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) Pb[qt][ks][e] = (__bf16)0.f;   // "P_{-1}": step 0 adds V_0 * 0
     }
-#undef RF2_STEP
-    // ---- last product: O += V P_{U-1} ------------------------------------------------------
+    rowmax(Sa, mxa);
+    slow = true;                                         // the first unit always sets the maximum
+    off_k = unit_off(4);
+    off_v = unit_off(2);
+    // step 0 reads "V part of unit -1" from slot 3 of the V ring, which nothing has filled yet:
+    // point it at finite data (the product is multiplied by zero probabilities)
+    dma_unit<C::NW, C::LPW>(vring + 3 * C::UNIT_BYTES, vbase + unit_off(0), wave, tid16);
+    wait_all_loads();
+
+    // ---- steady state ------------------------------------------------------------------------
+    for (int s = 0; s < U; s += 2) {
+      step(s, Sa, Sb, Pb, Pa, mxa, mxb);
+      if (s + 1 < U) step(s + 1, Sb, Sa, Pa, Pb, mxb, mxa);
+    }
+    // ---- last product: O += V P_{U-1} ----------------------------------------------------------
     ring_barrier<0>();
-    switch ((U - 1) & 3) {
-      case 0: pv(V0, Pa); break;
-      case 1: pv(V1, Pb); break;
-      case 2: pv(V2, Pa); break;
-      default: pv(V3, Pb); break;
+    {
+      const uint32_t v_addr = (uint32_t)((4 + ((U - 1) & 3)) * C::UNIT_BYTES) + v_lane;
+      if ((U - 1) & 1) {
+        float dummy[C::QT] = {};
+        (void)dummy;
+#pragma unroll
+        for (int g = NQ; g < NSLOT; ++g) {
+          const bf16x8 a = operand(0, v_addr, g);
+          const int dt = (g - NQ) / 2, ks = (g - NQ) % 2;
+#pragma unroll
+          for (int qt = 0; qt < C::QT; ++qt)
+            o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Pb[qt][ks], o[dt][qt], 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int g = NQ; g < NSLOT; ++g) {
+          const bf16x8 a = operand(0, v_addr, g);
+          const int dt = (g - NQ) / 2, ks = (g - NQ) % 2;
+#pragma unroll
+          for (int qt = 0; qt < C::QT; ++qt)
+            o[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Pa[qt][ks], o[dt][qt], 0, 0, 0);
+        }
+      }
     }
   }
 
   // ---- merge the two key halves and write the Q block -------------------------------------
   __syncthreads();                                        // every wavefront is done with the rings
-  float* ml = reinterpret_cast<float*>(V0);               // [wa][wc][qt][m|l][lane]: 4 KiB at most
+  float* ml = reinterpret_cast<float*>(vring);            // [wa][wc][qt][m|l][lane]: 4 KiB at most
   static_assert((BLK / 64) * 2 * C::QT * 2 * 64 * 4 <= C::UNIT_BYTES, "");
   float l_tot[C::QT];
 #pragma unroll
   for (int qt = 0; qt < C::QT; ++qt) {
-    l_tot[qt] = l_run[qt] + __shfl_xor(l_run[qt], 32);
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run[qt]), __float_as_uint(l_run[qt]), false, false);
+    l_tot[qt] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
     ml[(((wa * 2 + wc) * C::QT + qt) * 2 + 0) * 64 + lane] = m_run[qt];
     ml[(((wa * 2 + wc) * C::QT + qt) * 2 + 1) * 64 + lane] = l_tot[qt];
   }
@@ -373,15 +397,10 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     f_mine[qt] = l_all[qt] > 0.f ? w_mine / l_all[qt] : 0.f;   // a row with no kept key yields zeros
   }
   // The c=1 wavefront of each query half hands its scaled partial output to the c=0 one through
-  // the (now idle) K ring, in 8 KiB units of one (wa, dt) each.
+  // the (now idle) K ring, 8 KiB per (wa, dt).
   constexpr int XU_FLOATS = C::QT * 16 * 64;
-  constexpr int UPB = C::UNIT_BYTES / (XU_FLOATS * 4);    // exchange units per ring slot
-  static_assert(UPB >= 1 && (BLK / 64) * C::DT <= 4 * UPB, "exchange area must fit the K ring");
-  auto xunit = [&](int dt) -> float* {
-    const int u = wa * C::DT + dt, b = u / UPB;
-    unsigned char* base = b == 0 ? K0 : b == 1 ? K1 : b == 2 ? K2 : K3;
-    return reinterpret_cast<float*>(base) + (u % UPB) * XU_FLOATS;
-  };
+  static_assert((BLK / 64) * C::DT * XU_FLOATS * 4 <= 4 * C::UNIT_BYTES, "exchange area must fit the K ring");
+  auto xunit = [&](int dt) -> float* { return reinterpret_cast<float*>(kring) + (wa * C::DT + dt) * XU_FLOATS; };
   if (wc == 1) {
 #pragma unroll
     for (int dt = 0; dt < C::DT; ++dt)
