@@ -30,6 +30,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 template <int D, int BLK>
@@ -59,23 +60,39 @@ struct AttnCfg {
 // the only waits for it are the explicit vmcnt waits of ring_barrier below (its own
 // bookkeeping of direct-to-LDS loads runs out of slots with eight ring buffers and falls
 // back to waiting for every outstanding load before unrelated LDS reads).
-template <int NW, int LPW>
-__device__ __forceinline__ void dma_unit(unsigned char* lds, const unsigned char* g, int wave, uint32_t tid16) {
-  const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
-#pragma unroll
-  for (int u = 0; u < LPW; ++u) {
-    const uint32_t m0 = lds_base + (uint32_t)((u * NW + wave) * 1024);
-    const unsigned char* src = g + u * (NW * 1024) + tid16;
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m0), "v"(src) : "memory");
-  }
+// The S^T product is issued through assembly so that its accumulators are ordinary vector
+// registers: the compiler's own MFMA selection keeps every accumulator of this kernel in
+// the accumulation register file, from which the softmax arithmetic would need one copy
+// instruction per element.  The compiler does not know these statements are MFMAs, so the
+// wait states it would insert between the last MFMA of a chain and the first vector-ALU
+// read of its result are part of qk_last (18 >= the 12 that an 8-pass MFMA needs here).
+// Operands come from LDS reads and from the resident Q fragments, never from a preceding
+// vector-ALU write, and the accumulator is not touched by anything else in between.
+__device__ __forceinline__ void qk_first(f32x16& S, const bf16x8& a, const bf16x8& b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void qk_next(f32x16& S, const bf16x8& a, const bf16x8& b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void qk_last(f32x16& S0, f32x16& S1, const bf16x8& a, const bf16x8& b0, const bf16x8& b1) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %2, %3, %0\n\tv_mfma_f32_32x32x16_bf16 %1, %2, %4, %1\n\t"
+      "s_nop 7\n\ts_nop 7\n\ts_nop 1"
+      : "+v"(S0), "+v"(S1)
+      : "v"(a), "v"(b0), "v"(b1));
 }
 
 template <int NW>
 __device__ __forceinline__ void dma_one(unsigned char* lds, const unsigned char* g, int u, int wave, uint32_t tid16) {
   const uint32_t m0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds +
                       (uint32_t)((u * NW + wave) * 1024);
-  const unsigned char* src = g + u * (NW * 1024) + tid16;
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m0), "v"(src) : "memory");
+  const unsigned char* src = g + u * (NW * 1024);       // wavefront-uniform: scalar base + per-lane 32-bit offset
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(tid16), "s"(src) : "memory");
+}
+
+template <int NW, int LPW>
+__device__ __forceinline__ void dma_unit(unsigned char* lds, const unsigned char* g, int wave, uint32_t tid16) {
+#pragma unroll
+  for (int u = 0; u < LPW; ++u) dma_one<NW>(lds, g, u, wave, tid16);
 }
 
 __device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -161,7 +178,7 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
   constexpr int NQ = C::DS, NP = C::DT * 2, NSLOT = NQ + NP;
   constexpr int PD = 4;                                  // operand reads run this many slots ahead
   constexpr int EPS = 32 / NSLOT;                        // softmax elements handled per slot
-  static_assert(32 % NSLOT == 0 && 2 * C::LPW <= NSLOT, "slot plan");
+  static_assert(32 % NSLOT == 0 && EPS % 2 == 0 && NQ >= 2 && 2 * C::LPW <= NSLOT, "slot plan");
   auto operand = [&](uint32_t k_addr, uint32_t v_addr, int g) -> bf16x8 {
     if (g < NQ) return *reinterpret_cast<const bf16x8*>(ring + k_addr + g * 2048);   // chunk 2g+lh, row wc*32+l32
     const int dt = (g - NQ) / 2, ks = (g - NQ) % 2;      // key chunk wc*4 + 2ks + lh, channel 32dt + l32
@@ -256,18 +273,20 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     bf16x8 opnd[NSLOT];
 #pragma unroll
     for (int g = 0; g < PD; ++g) opnd[g] = operand(k_addr, v_addr, g);
+    off_k = unit_off(s + 5);      // list entries for the next step are fetched a step ahead
+    off_v = unit_off(s + 3);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int g = 0; g < NSLOT; ++g) {
       if (g + PD < NSLOT) opnd[g + PD] = operand(k_addr, v_addr, g + PD);
-      if (g < NQ) {
-#pragma unroll
-        for (int qt = 0; qt < C::QT; ++qt) {
-          if (g == 0) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) Snext[qt][i] = 0.f;
-          }
-          Snext[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[g], qf[qt][g], Snext[qt], 0, 0, 0);
-        }
+      if (g == 0) {
+        qk_first(Snext[0], opnd[g], qf[0][g]);
+        qk_first(Snext[1], opnd[g], qf[1][g]);
+      } else if (g < NQ - 1) {
+        qk_next(Snext[0], opnd[g], qf[0][g]);
+        qk_next(Snext[1], opnd[g], qf[1][g]);
+      } else if (g == NQ - 1) {
+        qk_last(Snext[0], Snext[1], opnd[g], qf[0][g], qf[1][g]);
       } else {
         const int dt = (g - NQ) / 2, ks = (g - NQ) % 2;
 #pragma unroll
@@ -276,15 +295,22 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
       }
       // softmax arithmetic of unit s: EPS of the 32 values of this lane per slot
 #pragma unroll
-      for (int e = g * EPS; e < (g + 1) * EPS; ++e) {
+      for (int e = g * EPS; e < (g + 1) * EPS; e += 2) {
         const int qt = e / 16, i = e % 16;
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[qt][i], scale_log2, -m_use[qt]));
-        rs[qt] += p;
-        Pcur[qt][i / 8][i % 8] = (__bf16)p;
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[qt][i], scale_log2, -m_use[qt]));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[qt][i + 1], scale_log2, -m_use[qt]));
+        const bf16x2 pk = {(__bf16)p0, (__bf16)p1};
+        rs[qt] += p0 + p1;   // (a bf16 dot-product instruction would halve the adds, but it stalls the MFMA pipe)
+        Pcur[qt][i / 8][i % 8] = pk[0];
+        Pcur[qt][i / 8][i % 8 + 1] = pk[1];
       }
       // one direct-to-LDS load per slot until both parts are on their way
       if (g < C::LPW) dma_one<C::NW>(k_dst, k_src, g, wave, tid16);
       else if (g < 2 * C::LPW) dma_one<C::NW>(v_dst, v_src, g - C::LPW, wave, tid16);
+      if (g == NQ + 1) rowmax(Snext, mxnext);            // S_{s+1} is complete since slot NQ-1
+      // Slots stay in this order: the operand reads keep their PD-slot lead over the MFMAs that
+      // consume them (left alone, the scheduler packs each read right in front of its consumer).
+      __builtin_amdgcn_sched_barrier(0);
     }
     // Keep the softmax arithmetic inside this block (its results are only consumed by the next
     // step, and the compiler would otherwise sink it there, out from under the MFMAs).
@@ -293,10 +319,7 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
       asm volatile("" : "+v"(Pcur[qt][0]), "+v"(Pcur[qt][1]), "+v"(rs[qt]));
       l_run[qt] += rs[qt];
     }
-    rowmax(Snext, mxnext);
     slow = need_slow(mxnext, s + 1);
-    off_k = unit_off(s + 5);      // list entries for the next step are fetched a step ahead
-    off_v = unit_off(s + 3);
   };
 
   if (U > 0) {
@@ -318,17 +341,24 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     float mxa[C::QT], mxb[C::QT];
     ring_barrier<0>();
 #pragma unroll
-    for (int qt = 0; qt < C::QT; ++qt) {
+    for (int ds = 0; ds < C::DS; ++ds) {
+      const bf16x8 a = operand(k_lane, 0, ds);
+      if (ds == 0) {
+        qk_first(Sa[0], a, qf[0][ds]);
+        qk_first(Sa[1], a, qf[1][ds]);
+      } else if (ds < C::DS - 1) {
+        qk_next(Sa[0], a, qf[0][ds]);
+        qk_next(Sa[1], a, qf[1][ds]);
+      } else {
+        qk_last(Sa[0], Sa[1], a, qf[0][ds], qf[1][ds]);
+      }
+    }
 #pragma unroll
-      for (int i = 0; i < 16; ++i) Sa[qt][i] = 0.f;
-#pragma unroll
-      for (int ds = 0; ds < C::DS; ++ds)
-        Sa[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(operand(k_lane, 0, ds), qf[qt][ds], Sa[qt], 0, 0, 0);
+    for (int qt = 0; qt < C::QT; ++qt)
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int e = 0; e < 8; ++e) Pb[qt][ks][e] = (__bf16)0.f;   // "P_{-1}": step 0 adds V_0 * 0
-    }
     rowmax(Sa, mxa);
     slow = true;                                         // the first unit always sets the maximum
     off_k = unit_off(4);
