@@ -1,0 +1,125 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times.
+
+The oracle cannot run whole 75K-token layers in seconds, so it checks: permutation and
+pooling of sampled heads in full, the block mask of sampled heads in full, attention on
+sampled Q blocks (first, last/ragged, a sink row, the block straddling body and sink, a few
+seeded random ones) with every one of their rows, plus properties that hold at any size.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rf2_oracle as orc
+from paper_2512_24086_amd import inputs
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+CASES = {
+    # name: (workload, sparsity, sampled heads)
+    "video720p": ("video720p", 0.8, (0, 17, 39)),
+    "video480p": ("video480p", 0.8, (3, 38)),
+    "image": ("image", 0.5, (0, 23)),
+    "longvideo_s90": ("longvideo", 0.9, (11,)),
+    "longvideo_s50": ("longvideo", 0.5, (5,)),
+}
+
+
+@pytest.fixture(scope="module", params=list(CASES), ids=list(CASES))
+def big(request):
+    name, s, heads = CASES[request.param]
+    wl = inputs.WORKLOADS[name]
+    print(f"\n[case] {request.param}: {wl.name} N={wl.N} heads={wl.heads} sparsity={s} sampled heads {heads}", flush=True)
+    plan = hp.make_plan(wl, sparsity=s)
+    q, k, v = inputs.make_qkv(wl, device=DEV)
+    buf = plan.alloc(DEV)
+    plan.layer(q, k, v, buf)
+    torch.cuda.synchronize()
+    i, c = plan.info, plan.cfg
+    rng = np.random.default_rng(wl.index)
+    blocks = sorted({0, i.n_blocks - 1, *rng.integers(0, i.n_blocks, 4).tolist()} |
+                    ({i.sink_block_begin, i.n_blocks - 2} if i.sink_block_end > i.sink_block_begin else set()))
+    ref = {}
+    for h in heads:
+        Q, K, V = (hp.f64(x[0, h].cpu()) for x in (q, k, v))
+        perm = orc.perm_table(c.T, c.H, c.W, i.wt, i.wh, i.ww, c.sink_frames, bool(c.sink_at_end))
+        Qp, Kp, Vp = orc.permute(Q, perm), orc.permute(K, perm), orc.permute(V, perm)
+        qbar, kbar = orc.pool_blocks(Qp, c.block), orc.pool_blocks(Kp, c.block)
+        S_hat = orc.block_scores(qbar, kbar)
+        M = orc.select_blocks(S_hat, i.k_sel, i.sink_block_begin, i.sink_block_end)
+        gap = orc.selection_gap(S_hat, i.k_sel, i.sink_block_begin, i.sink_block_end)
+        ref[h] = dict(perm=perm, Qp=Qp, Kp=Kp, Vp=Vp, qbar=qbar, kbar=kbar, M=M, gap=gap)
+        print(f"[oracle] head {h} done", flush=True)
+    yield wl, plan, (q, k, v), buf, ref, blocks
+    plan.close()
+
+
+def test_permutation_and_pooling(big):
+    wl, plan, (q, k, v), buf, ref, _ = big
+    N = plan.info.N
+    for h, r in ref.items():
+        qp = inputs.bf16_bits(buf["qp"][0, h])
+        kp = hp.kp_to_rows(inputs.bf16_bits(buf["kp"][0, h]))
+        vp = hp.vp_to_rows(inputs.bf16_bits(buf["vp"][0, h]))
+        for got, src in ((qp, q), (kp, k), (vp, v)):
+            assert np.array_equal(got[:N], inputs.bf16_bits(src[0, h])[r["perm"]])
+            assert (got[N:] == 0).all()
+        for name in ("qbar", "kbar"):
+            assert np.abs(buf[name][0, h].double().cpu().numpy() - r[name]).max() < 2e-6
+
+
+def test_block_mask(big):
+    wl, plan, _, buf, ref, _ = big
+    i = plan.info
+    Tb = i.n_blocks
+    sink = np.zeros(Tb, dtype=bool)
+    sink[i.sink_block_begin:i.sink_block_end] = True
+    # properties over ALL heads: row counts, ascending in-range lists, sink columns present
+    cnt = buf["blk_cnt"][0].cpu().numpy()
+    idx = buf["blk_idx"][0].cpu().numpy()
+    assert (cnt[:, sink] == Tb).all() and (cnt[:, ~sink] == (i.k_row if i.k_row < Tb else Tb)).all()
+    rows = idx[:, ~sink, :]
+    if i.k_row < Tb:
+        assert (np.diff(rows, axis=-1) > 0).all() and rows.min() >= 0 and rows.max() < Tb
+        n_sink = i.sink_block_end - i.sink_block_begin
+        if n_sink:                                   # sink blocks sit at the end of the sequence: last entries of each list
+            assert (rows[..., -n_sink:] == np.arange(i.sink_block_begin, i.sink_block_end)).all()
+    near = 0
+    for h, r in ref.items():
+        M = hp.gpu_lists_to_mask(buf["blk_idx"][0, h], buf["blk_cnt"][0, h], Tb)
+        clear = r["gap"] > hp.TIE_GAP
+        near += int((~clear & ~sink).sum())
+        assert np.array_equal(M[clear], r["M"][clear])
+        assert (M.sum(1) == r["M"].sum(1)).all()
+    print(f"[mask] near-tie rows exempted: {near} of {len(ref) * int((~sink).sum())}")
+
+
+def test_attention_on_sampled_blocks(big):
+    wl, plan, _, buf, ref, blocks = big
+    i, b = plan.info, plan.cfg.block
+    worst = (0.0, 0.0)
+    for h, r in ref.items():
+        M = hp.gpu_lists_to_mask(buf["blk_idx"][0, h], buf["blk_cnt"][0, h], i.n_blocks)   # the mask the GPU used
+        want = orc.block_sparse_attention(r["Qp"], r["Kp"], r["Vp"], M, b, q_blocks=blocks)
+        got = hp.f64(buf["op"][0, h].cpu())[:i.N]
+        rows = ~np.isnan(want[:, 0])
+        err = np.abs(got[rows] - want[rows])
+        assert err.max() <= hp.ATTN_MAX_ABS and err.mean() <= hp.ATTN_MEAN_ABS, (h, err.max(), err.mean())
+        worst = (max(worst[0], err.max()), max(worst[1], err.mean()))
+        # the unpermuted output is a bit-exact scatter of the permuted one
+        o_bits = inputs.bf16_bits(buf["o"][0, h])
+        assert np.array_equal(o_bits[r["perm"]], inputs.bf16_bits(buf["op"][0, h])[:i.N])
+    print(f"[attention] blocks {blocks}: max abs {worst[0]:.2e}, mean abs {worst[1]:.2e}")
+
+
+def test_constant_values_give_constant_output(big):
+    """V == 1 everywhere must give O == 1 on every row of every head (probabilities sum to one)."""
+    wl, plan, (q, k, v), buf, _, _ = big
+    ones = torch.ones_like(v)
+    plan.rf2_permute(q, k, ones, buf["qp"], buf["kp"], buf["vp"])
+    plan.rf2_block_sparse_attn(buf["qp"], buf["kp"], buf["vp"], buf["blk_idx"], buf["blk_cnt"], buf["op"])
+    plan.rf2_unpermute(buf["op"], buf["o"])
+    torch.cuda.synchronize()
+    dev = (buf["o"].float() - 1.0).abs().max().item()
+    assert dev <= 2 ** -7, dev                      # bf16 rounding of the probabilities and of the output
