@@ -27,7 +27,7 @@ METRIC = "ms/layer + effective TFLOPS of block-sparse attn @80% sparsity, 75.6K 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 # HBM bytes per launch of the attention kernel on the headline workload, from the rocprofv3 --pmc
 # runs summarised in profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel); None = not measured.
-ATTN_TRAFFIC_BYTES = {"video720p": None}
+ATTN_TRAFFIC_BYTES = {"video720p": 9.09e10}   # profiles/block_sparse_attn_video720p.md
 
 
 def ensure_library():
@@ -96,10 +96,9 @@ def time_sdpa(q, k, v, iters=2):
 
 def cpu_baseline(wl, plan, q, k, v, dense_flops):
     """The fp64 oracle, untuned, on a bounded sample: all stages for ONE head up to the mask, attention
-    for a few Q blocks of that head; extrapolated to the whole layer by head count and kept pairs."""
+    for the Q blocks of that head; extrapolated to the whole layer by head count and kept pairs."""
     from oracle import rf2_oracle as orc
     from threadpoolctl import threadpool_info
-    import numpy as np
     i, c = plan.info, plan.cfg
     head = 0
     Q, K, V = (orc.bf16_bits_to_f64(inputs.bf16_bits(x[0, head])) for x in (q, k, v))
@@ -110,8 +109,7 @@ def cpu_baseline(wl, plan, q, k, v, dense_flops):
     M = orc.select_blocks(S_hat, i.k_sel, i.sink_block_begin, i.sink_block_end)
     t_pre = time.perf_counter() - t0
     Tb = i.n_blocks
-    rng = np.random.default_rng(0)
-    sample = sorted({0, Tb - 1, i.sink_block_begin, *rng.integers(0, Tb, 5).tolist()})
+    sample = list(range(Tb))                           # every Q block of this one head: ~10 s of oracle time
     t0 = time.perf_counter()
     Op = orc.block_sparse_attention(Qp, Kp, Vp, M, c.block, q_blocks=sample)
     t_attn = time.perf_counter() - t0
