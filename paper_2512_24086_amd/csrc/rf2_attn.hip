@@ -81,18 +81,26 @@ __device__ __forceinline__ void qk_last(f32x16& S0, f32x16& S1, const bf16x8& a,
       : "v"(a), "v"(b0), "v"(b1));
 }
 
-template <int NW>
-__device__ __forceinline__ void dma_one(unsigned char* lds, const unsigned char* g, int u, int wave, uint32_t tid16) {
-  const uint32_t m0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds +
-                      (uint32_t)((u * NW + wave) * 1024);
-  const unsigned char* src = g + u * (NW * 1024);       // wavefront-uniform: scalar base + per-lane 32-bit offset
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(tid16), "s"(src) : "memory");
+// Tells the compiler that a pointer is the same in every lane (it then lives in scalar registers).
+__device__ __forceinline__ const unsigned char* uniform_ptr(const void* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const unsigned char*)(((uint64_t)hi << 32) | lo);
 }
 
+// One wavefront-wide direct-to-LDS load: 64 x 16 B from g + voff (scalar base, per-lane 32-bit
+// byte offset) to the KiB of LDS at `lds_kib`.
+__device__ __forceinline__ void dma_one(uint32_t lds_kib, const unsigned char* g, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_kib), "v"(voff), "s"(g) : "memory");
+}
+
+// A whole unit part (LPW KiB per wavefront): wavefront w takes KiB u*NW + w for u = 0..LPW-1.
 template <int NW, int LPW>
 __device__ __forceinline__ void dma_unit(unsigned char* lds, const unsigned char* g, int wave, uint32_t tid16) {
+  const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
+  g = uniform_ptr(g);
 #pragma unroll
-  for (int u = 0; u < LPW; ++u) dma_one<NW>(lds, g, u, wave, tid16);
+  for (int u = 0; u < LPW; ++u) dma_one(lds_base + (uint32_t)((u * NW + wave) * 1024), g + u * (NW * 1024), tid16);
 }
 
 __device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -114,7 +122,7 @@ template <int D, int BLK>
 __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     const __bf16* __restrict__ qp, const __bf16* __restrict__ kp, const __bf16* __restrict__ vp,
     const int32_t* __restrict__ blk_idx, const int32_t* __restrict__ blk_cnt, __bf16* __restrict__ op,
-    float* __restrict__ lse, const int32_t* __restrict__ row_order, int rows_per_xcd, int Tb, int k_row,
+    float* __restrict__ lse, const int32_t* __restrict__ row_order, int sink_per_xcd, int plain_per_xcd, int n_bh, int Tb, int k_row,
     int last_valid, float scale_log2) {
   using C = AttnCfg<D, BLK>;
   // Rings of 4 K parts (slots 0-3) and 4 V^T parts (slots 4-7); unit x uses slot x % 4 of each.
@@ -123,9 +131,29 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
   unsigned char* const vring = ring + 4 * C::UNIT_BYTES;
 
   // ---- which Q block ---------------------------------------------------------------
+  // Slots of an XCD, in issue order: the all-column sink rows are several times longer than
+  // ordinary rows, so the sink rows of head h are issued LEAD heads ahead of its ordinary rows
+  // (sink(0..LEAD-1), then sink(h+LEAD), plain(h) for each h, then the last plain rows): no long
+  // row is left running alone at the end, while only a few heads' K/V are live at a time.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int bh = slot / rows_per_xcd;
-  const int qi = row_order[xcd * rows_per_xcd + slot % rows_per_xcd];
+  const int lead = min(2, n_bh), both = sink_per_xcd + plain_per_xcd;
+  int bh, entry;
+  if (slot < lead * sink_per_xcd) {
+    bh = slot / sink_per_xcd;
+    entry = slot % sink_per_xcd;
+  } else {
+    const int t = slot - lead * sink_per_xcd;
+    if (t < (n_bh - lead) * both) {
+      const int ph = t / both, r = t % both;
+      bh = r < sink_per_xcd ? ph + lead : ph;
+      entry = r;
+    } else {
+      const int u = t - (n_bh - lead) * both;
+      bh = n_bh - lead + u / plain_per_xcd;
+      entry = sink_per_xcd + u % plain_per_xcd;
+    }
+  }
+  const int qi = row_order[xcd * (sink_per_xcd + plain_per_xcd) + entry];
   if (qi < 0) return;
   const size_t row_id = (size_t)bh * Tb + qi;
   int cnt = blk_cnt[row_id];
@@ -140,8 +168,8 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
   const int wa = wave >> 1, wc = wave & 1;
   const int l32 = lane & 31, lh = lane >> 5;
   const size_t head_off = (size_t)bh * Tb * BLK * D;    // elements; same for qp, kp, vp, op
-  const unsigned char* __restrict__ kbase = reinterpret_cast<const unsigned char*>(kp + head_off);
-  const unsigned char* __restrict__ vbase = reinterpret_cast<const unsigned char*>(vp + head_off);
+  const unsigned char* const kbase = uniform_ptr(kp + head_off);
+  const unsigned char* const vbase = uniform_ptr(vp + head_off);
   // LDS byte offsets of this lane's first operand chunk inside a K part / a V^T part
   const uint32_t k_lane = (uint32_t)((lh * 64 + wc * 32 + l32) * 16);
   const uint32_t v_lane = (uint32_t)(((wc * 4 + lh) * D + l32) * 16);
@@ -149,12 +177,20 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     const int j = dense ? it : list[it];
     return min(max(j, 0), Tb - 1);                      // a corrupt list can give wrong results, never a fault
   };
-  // global byte offset of unit x's part inside kp / vp of this head (x clamped: loads past the
-  // end re-fetch the last unit into a free slot, which keeps the outstanding-load count uniform)
-  auto unit_off = [&](int x) {
-    x = min(x, U - 1);
-    return (size_t)block_at(x / C::KT) * C::TILE_BYTES + (size_t)(x % C::KT) * C::UNIT_BYTES;
+  // Byte offset of unit x's part inside kp / vp of this head (x clamped: loads past the end
+  // re-fetch the last unit into a free slot, which keeps the outstanding-load count uniform).
+  // The list entry is read one step before it is needed (list_entry), and turned into an offset
+  // only when it is used (part_off), so that no step waits for a scalar memory load.
+  auto list_entry = [&](int x) {
+    const int it = min(x, U - 1) / C::KT;
+    return dense ? it : list[it];
   };
+  auto part_off = [&](int entry, int x) {
+    const int j = min(max(entry, 0), Tb - 1);            // a corrupt list can give wrong results, never a fault
+    return (uint32_t)j * (uint32_t)C::TILE_BYTES + (uint32_t)(min(x, U - 1) % C::KT) * (uint32_t)C::UNIT_BYTES;
+  };
+  auto unit_off = [&](int x) { return (size_t)part_off(list_entry(x), x); };
+  const uint32_t ring_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)ring;
   // Only the last listed block can be the ragged last block of the sequence (lists ascend).
   int partial_begin = U;
   if (U > 0 && last_valid < BLK && block_at(cnt - 1) == Tb - 1) partial_begin = (cnt - 1) * C::KT;
@@ -249,7 +285,7 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     }
   };
 
-  size_t off_k = 0, off_v = 0;
+  int entry_k = 0, entry_v = 0;                          // list entries of the units loaded by the next step
   bool slow = true;
   // Step s: products S_{s+1} and V P_{s-1} around the softmax arithmetic of unit s (eqs. 2, 3),
   // the loads of the K part of unit s+4 and the V^T part of unit s+2 spread between them, and
@@ -260,10 +296,14 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     const uint32_t k_addr = (uint32_t)(((s + 1) & 3) * C::UNIT_BYTES) + k_lane;                        // K part of unit s+1
     const uint32_t v_addr = (uint32_t)((4 + ((s + 3) & 3)) * C::UNIT_BYTES) + v_lane;                  // V^T part of unit s-1
     if (slow) slow_path(Scur, mxcur, Pprev, v_addr, s);
-    unsigned char* const k_dst = kring + (s & 3) * C::UNIT_BYTES;                                      // slot of unit s+4
-    unsigned char* const v_dst = vring + ((s + 2) & 3) * C::UNIT_BYTES;                                // slot of unit s+2
-    const unsigned char* const k_src = kbase + off_k;
-    const unsigned char* const v_src = vbase + off_v;
+    // direct-to-LDS loads of this step: K part of unit s+4 -> slot s % 4, V^T part of unit s+2 -> slot (s+2) % 4
+    const uint32_t k_dst = ring_lds + (uint32_t)((s & 3) * C::UNIT_BYTES + wave * 1024);
+    const uint32_t v_dst = ring_lds + (uint32_t)((4 + ((s + 2) & 3)) * C::UNIT_BYTES + wave * 1024);
+    const uint32_t k_voff = tid16 + part_off(entry_k, s + 4);
+    const uint32_t v_voff = tid16 + part_off(entry_v, s + 2);
+    // the entries fetched by the previous step are consumed before the next fetches are issued:
+    // scalar loads return out of order, so a wait for the old ones would also wait for new ones
+    __builtin_amdgcn_sched_barrier(0);
     float m_use[C::QT], rs[C::QT];
 #pragma unroll
     for (int qt = 0; qt < C::QT; ++qt) {
@@ -273,8 +313,8 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     bf16x8 opnd[NSLOT];
 #pragma unroll
     for (int g = 0; g < PD; ++g) opnd[g] = operand(k_addr, v_addr, g);
-    off_k = unit_off(s + 5);      // list entries for the next step are fetched a step ahead
-    off_v = unit_off(s + 3);
+    entry_k = list_entry(s + 5);  // for the next step
+    entry_v = list_entry(s + 3);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int g = 0; g < NSLOT; ++g) {
@@ -305,8 +345,8 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
         Pcur[qt][i / 8][i % 8 + 1] = pk[1];
       }
       // one direct-to-LDS load per slot until both parts are on their way
-      if (g < C::LPW) dma_one<C::NW>(k_dst, k_src, g, wave, tid16);
-      else if (g < 2 * C::LPW) dma_one<C::NW>(v_dst, v_src, g - C::LPW, wave, tid16);
+      if (g < C::LPW) dma_one(k_dst + g * (C::NW * 1024), kbase + g * (C::NW * 1024), k_voff);
+      else if (g < 2 * C::LPW) dma_one(v_dst + (g - C::LPW) * (C::NW * 1024), vbase + (g - C::LPW) * (C::NW * 1024), v_voff);
       if (g == NQ + 1) rowmax(Snext, mxnext);            // S_{s+1} is complete since slot NQ-1
       // Slots stay in this order: the operand reads keep their PD-slot lead over the MFMAs that
       // consume them (left alone, the scheduler packs each read right in front of its consumer).
@@ -361,8 +401,8 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
         for (int e = 0; e < 8; ++e) Pb[qt][ks][e] = (__bf16)0.f;   // "P_{-1}": step 0 adds V_0 * 0
     rowmax(Sa, mxa);
     slow = true;                                         // the first unit always sets the maximum
-    off_k = unit_off(4);
-    off_v = unit_off(2);
+    entry_k = list_entry(4);
+    entry_v = list_entry(2);
     // step 0 reads "V part of unit -1" from slot 3 of the V ring, which nothing has filled yet:
     // point it at finite data (the product is multiplied by zero probabilities)
     dma_unit<C::NW, C::LPW>(vring + 3 * C::UNIT_BYTES, vbase + unit_off(0), wave, tid16);
@@ -472,9 +512,11 @@ int launch_attn(const rf2_plan* plan, const void* qp, const void* kp, const void
   const rf2_info& in = plan->info;
   auto kern = block_sparse_attn_kernel<D, BLK>;
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
-  const unsigned grid = 8u * (unsigned)plan->rows_per_xcd * (unsigned)(c.batch * c.heads);
+  const int n_bh = c.batch * c.heads;
+  const unsigned grid = 8u * (unsigned)(plan->sink_per_xcd + plan->plain_per_xcd) * (unsigned)n_bh;
   kern<<<dim3(grid), dim3(C::NT), 0, st>>>((const __bf16*)qp, (const __bf16*)kp, (const __bf16*)vp, blk_idx,
-                                                     blk_cnt, (__bf16*)op, lse, plan->d_row_order, plan->rows_per_xcd,
+                                                     blk_cnt, (__bf16*)op, lse, plan->d_row_order, plan->sink_per_xcd,
+                                       plan->plain_per_xcd, n_bh,
                                                      in.n_blocks, in.k_row, in.last_block_valid, scale_log2);
   RF2_LAUNCH_CHECK();
   return RF2_OK;

@@ -153,25 +153,27 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
         p->perm[(size_t)pos] = (int32_t)n;
       }
 
-  // Work order of the attention kernel.  Workgroup g runs on XCD g % 8; each XCD gets a
-  // contiguous range of a head's ordinary Q blocks (neighbouring blocks tend to pick the
-  // same K blocks, so they share that XCD's L2) and its share of the long all-column sink
-  // rows, which are placed first so the long rows start early.
+  // Work tables of the attention kernel.  Workgroup g runs on XCD g % 8.  A head's all-column
+  // sink rows are dealt round-robin to the XCDs; each XCD also gets a contiguous range of the
+  // head's ordinary Q blocks (neighbouring blocks tend to pick the same K blocks, so they share
+  // its L2).  The kernel decides the issue order of the two kinds (sink rows run ahead).
   const int sb = in.sink_block_begin, se = in.sink_block_end;
-  std::vector<std::vector<int32_t>> per_xcd(8);
-  for (int i = sb; i < se; ++i) per_xcd[(i - sb) % 8].push_back(i);
+  std::vector<std::vector<int32_t>> sink_xcd(8), plain_xcd(8);
+  for (int i = sb; i < se; ++i) sink_xcd[(i - sb) % 8].push_back(i);
   const int n_plain = Tb - nS;
   for (int r = 0; r < n_plain; ++r) {
     const int i = r < sb ? r : r + nS;
-    const int x = (int)(((int64_t)r * 8) / std::max(n_plain, 1));
-    per_xcd[x].push_back(i);
+    plain_xcd[(int)(((int64_t)r * 8) / std::max(n_plain, 1))].push_back(i);
   }
-  size_t longest = 0;
-  for (auto& v : per_xcd) longest = std::max(longest, v.size());
-  p->rows_per_xcd = (int32_t)longest;
-  std::vector<int32_t> order(8 * longest, -1);
-  for (int x = 0; x < 8; ++x)
-    for (size_t r = 0; r < per_xcd[x].size(); ++r) order[x * longest + r] = per_xcd[x][r];
+  size_t spx = 0, ppx = 0;
+  for (int x = 0; x < 8; ++x) { spx = std::max(spx, sink_xcd[x].size()); ppx = std::max(ppx, plain_xcd[x].size()); }
+  p->sink_per_xcd = (int32_t)spx;
+  p->plain_per_xcd = (int32_t)ppx;
+  std::vector<int32_t> order(8 * (spx + ppx), -1);      // [xcd][sink slots | plain slots], -1 = no work
+  for (int x = 0; x < 8; ++x) {
+    for (size_t r = 0; r < sink_xcd[x].size(); ++r) order[x * (spx + ppx) + r] = sink_xcd[x][r];
+    for (size_t r = 0; r < plain_xcd[x].size(); ++r) order[x * (spx + ppx) + spx + r] = plain_xcd[x][r];
+  }
 
   std::vector<int32_t> perm_pad((size_t)in.N_pad, -1);
   std::memcpy(perm_pad.data(), p->perm.data(), (size_t)N * sizeof(int32_t));
