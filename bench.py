@@ -37,8 +37,10 @@ def ensure_library():
     rf2.lib()
 
 
-def time_layer(plan, q, k, v, buf, steps, warmup):
-    """Times `steps` whole layers (wall clock between device syncs) and each stage (events)."""
+def time_layer(plan, q, k, v, buf, steps, warmup, fused=True):
+    """Times `steps` whole layers (wall clock between device syncs) and each stage (events).
+    fused: the inverse permutation happens in the attention kernel's epilogue (3 launches per layer);
+    otherwise attention writes the permuted output and rf2_unpermute follows (4 launches)."""
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
 
     def one(marks=None):
@@ -47,9 +49,14 @@ def time_layer(plan, q, k, v, buf, steps, warmup):
         if marks: marks[1].record()
         plan.rf2_predict_mask(buf["qbar"], buf["kbar"], buf["blk_idx"], buf["blk_cnt"])
         if marks: marks[2].record()
-        plan.rf2_block_sparse_attn(buf["qp"], buf["kp"], buf["vp"], buf["blk_idx"], buf["blk_cnt"], buf["op"])
-        if marks: marks[3].record()
-        plan.rf2_unpermute(buf["op"], buf["o"])
+        if fused:
+            plan.rf2_block_sparse_attn_unpermuted(buf["qp"], buf["kp"], buf["vp"], buf["blk_idx"], buf["blk_cnt"],
+                                                  buf["o"])
+            if marks: marks[3].record()
+        else:
+            plan.rf2_block_sparse_attn(buf["qp"], buf["kp"], buf["vp"], buf["blk_idx"], buf["blk_cnt"], buf["op"])
+            if marks: marks[3].record()
+            plan.rf2_unpermute(buf["op"], buf["o"])
         if marks: marks[4].record()
 
     for _ in range(warmup):
@@ -136,6 +143,8 @@ def main():
     ap.add_argument("--sparsity", type=float, default=None)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention baselines")
+    ap.add_argument("--unfused", action="store_true",
+                    help="time rf2_block_sparse_attn + rf2_unpermute instead of the fused entry point")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU kernel path; run with --gpus 1 "
@@ -155,17 +164,18 @@ def main():
     buf = plan.alloc("cuda")
     torch.cuda.synchronize()
 
-    wall_ms, stages = time_layer(plan, q, k, v, buf, args.steps, args.warmup)
+    wall_ms, stages = time_layer(plan, q, k, v, buf, args.steps, args.warmup, fused=not args.unfused)
     bh = wl.batch * wl.heads
     dense_flops = 4.0 * wl.N * wl.N * wl.head_dim * bh
     kept_flops = 4.0 * wl.block * wl.block * wl.head_dim * i.kept_pairs_per_head * bh
     attn_ms = stages["block_sparse_attn"]
     itemsize = 2
     tensor_bytes = bh * wl.N * wl.head_dim * itemsize
-    gbps = {
-        "permute_pool": (6 * tensor_bytes) / (stages["permute_pool"] * 1e-3) / 1e9,
-        "unpermute": (2 * tensor_bytes) / (stages["unpermute"] * 1e-3) / 1e9,
-    }
+    gbps = {"permute_pool": (6 * tensor_bytes) / (stages["permute_pool"] * 1e-3) / 1e9}
+    if args.unfused:
+        gbps["unpermute"] = (2 * tensor_bytes) / (stages["unpermute"] * 1e-3) / 1e9
+    else:
+        stages["unpermute"] = 0.0          # done by the attention kernel's epilogue
     out = {
         "metric": METRIC, "value": dense_flops / (wall_ms * 1e-3) / 1e12,
         "unit": "TFLOP/s dense-equivalent (4*N^2*d*heads per layer / whole-layer time)",
@@ -174,7 +184,8 @@ def main():
         "config": {"workload": f"{wl.name}: B{wl.batch} x {wl.heads} heads x d{wl.head_dim}, grid {wl.T}x{wl.H}x{wl.W}"
                                f" = {wl.N} tokens, block {wl.block}, sparsity {s}, sink_frames {wl.sink_frames}",
                    "n_blocks": i.n_blocks, "k_row": i.k_row, "kept_pairs_per_head": i.kept_pairs_per_head,
-                   "achieved_sparsity": round(i.achieved_sparsity, 4)},
+                   "achieved_sparsity": round(i.achieved_sparsity, 4),
+                   "inverse_permutation": "rf2_unpermute" if args.unfused else "fused into the attention epilogue"},
         "stages_ms": {n: round(t, 4) for n, t in stages.items()},
         "stages_gbps": {n: round(g, 1) for n, g in gbps.items()},
         "attn": {"ms": round(attn_ms, 4), "kept_tflops": round(kept_flops / (attn_ms * 1e-3) / 1e12, 1),

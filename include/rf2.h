@@ -149,9 +149,12 @@ int rf2_predict_mask(const rf2_plan* plan, const float* qbar, const float* kbar,
  *   qp, kp, vp : as written by rf2_permute                                 (in)
  *   blk_idx, blk_cnt : any valid list in the rf2_predict_mask format: row stride
  *             k_row, entries ascending, distinct, in [0, Tb), count in [1, k_row]
- *             or == Tb (then the list is ignored and all blocks are used).
- *             Entries are NOT checked on the device: an index outside [0, Tb)
- *             is undefined behaviour.                                      (in)
+ *             or == Tb (then the list is ignored and all blocks are used).  A count
+ *             of 0 yields zero output rows and lse = -inf; counts above k_row are
+ *             clamped to k_row, entries outside [0, Tb) to the nearest valid block
+ *             (wrong values, never a fault).  Keys past N are masked only when the
+ *             ragged last block is the LAST entry of its list, as it is in ascending
+ *             lists.                                                       (in)
  *   op      : [B, Hh, N_pad, d] bf16 in permuted order; rows >= N unspecified (out)
  *   lse     : optional [B, Hh, N_pad] fp32 natural-log sum-exp of the scaled
  *             logits over the kept keys, may be NULL                       (out)
@@ -159,6 +162,17 @@ int rf2_predict_mask(const rf2_plan* plan, const float* qbar, const float* kbar,
 int rf2_block_sparse_attn(const rf2_plan* plan, const void* qp, const void* kp, const void* vp,
                           const int32_t* blk_idx, const int32_t* blk_cnt, void* op, float* lse,
                           void* stream);
+
+/*
+ * The same attention with the inverse permutation fused into its epilogue (the layer then
+ * needs no rf2_unpermute and no op buffer): row p of the result goes to token perm[p].
+ *   o   : [B, Hh, N, d] bf16, tokens in [T, H, W] raster order            (out)
+ *   lse : optional [B, Hh, N] fp32, raster order, may be NULL              (out)
+ * All other arguments as for rf2_block_sparse_attn; the values written are identical.
+ */
+int rf2_block_sparse_attn_unpermuted(const rf2_plan* plan, const void* qp, const void* kp, const void* vp,
+                                     const int32_t* blk_idx, const int32_t* blk_cnt, void* o, float* lse,
+                                     void* stream);
 
 /* o[perm[p]] = op[p] for p < N.  op: [B, Hh, N_pad, d] bf16; o: [B, Hh, N, d] bf16. */
 int rf2_unpermute(const rf2_plan* plan, const void* op, void* o, void* stream);

@@ -123,7 +123,7 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     const __bf16* __restrict__ qp, const __bf16* __restrict__ kp, const __bf16* __restrict__ vp,
     const int32_t* __restrict__ blk_idx, const int32_t* __restrict__ blk_cnt, __bf16* __restrict__ op,
     float* __restrict__ lse, const int32_t* __restrict__ row_order, int sink_per_xcd, int plain_per_xcd, int n_bh, int Tb, int k_row,
-    int last_valid, float scale_log2) {
+    int last_valid, float scale_log2, const int32_t* __restrict__ scatter, int n_tokens) {
   using C = AttnCfg<D, BLK>;
   // Rings of 4 K parts (slots 0-3) and 4 V^T parts (slots 4-7); unit x uses slot x % 4 of each.
   __shared__ __attribute__((aligned(1024))) unsigned char ring[8 * C::UNIT_BYTES];
@@ -484,7 +484,10 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
 #pragma unroll
     for (int qt = 0; qt < C::QT; ++qt) {
       const size_t row = (size_t)qi * BLK + 64 * wa + 32 * qt + l32;
-      __bf16* orow = op + head_off + row * D;
+      // plain output: row `row` of the permuted layout; fused inverse permutation: the token's raster row
+      const int target = scatter ? scatter[row] : (int)row;
+      if (target < 0) continue;                              // padding row of the last block
+      __bf16* orow = scatter ? op + ((size_t)bh * n_tokens + target) * D : op + head_off + row * D;
 #pragma unroll
       for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
@@ -499,14 +502,15 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
           *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g + 4 * lh) = pk;
         }
       if (lse != nullptr && lh == 0)
-        lse[(size_t)bh * Tb * BLK + row] = m_all[qt] * 0.6931471805599453f + __logf(l_all[qt]);
+        lse[scatter ? (size_t)bh * n_tokens + target : (size_t)bh * Tb * BLK + row] =
+            m_all[qt] * 0.6931471805599453f + __logf(l_all[qt]);
     }
   }
 }
 
 template <int D, int BLK>
 int launch_attn(const rf2_plan* plan, const void* qp, const void* kp, const void* vp, const int32_t* blk_idx,
-                const int32_t* blk_cnt, void* op, float* lse, hipStream_t st) {
+                const int32_t* blk_cnt, void* op, float* lse, bool scatter, hipStream_t st) {
   using C = AttnCfg<D, BLK>;
   const rf2_config& c = plan->cfg;
   const rf2_info& in = plan->info;
@@ -517,9 +521,23 @@ int launch_attn(const rf2_plan* plan, const void* qp, const void* kp, const void
   kern<<<dim3(grid), dim3(C::NT), 0, st>>>((const __bf16*)qp, (const __bf16*)kp, (const __bf16*)vp, blk_idx,
                                                      blk_cnt, (__bf16*)op, lse, plan->d_row_order, plan->sink_per_xcd,
                                        plan->plain_per_xcd, n_bh,
-                                                     in.n_blocks, in.k_row, in.last_block_valid, scale_log2);
+                                                     in.n_blocks, in.k_row, in.last_block_valid, scale_log2,
+                                                     scatter ? plan->d_perm : nullptr, (int)in.N);
   RF2_LAUNCH_CHECK();
   return RF2_OK;
+}
+
+int dispatch_attn(const rf2_plan* plan, const void* qp, const void* kp, const void* vp, const int32_t* blk_idx,
+                  const int32_t* blk_cnt, void* out, float* lse, bool scatter, void* stream) {
+  if (!plan || !qp || !kp || !vp || !blk_idx || !blk_cnt || !out) return RF2_ERR_INVALID_ARG;
+  if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
+  const rf2_config& c = plan->cfg;
+  hipStream_t st = (hipStream_t)stream;
+  if (c.head_dim == 128 && c.block == 128) return launch_attn<128, 128>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
+  if (c.head_dim == 64 && c.block == 64) return launch_attn<64, 64>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
+  if (c.head_dim == 128 && c.block == 64) return launch_attn<128, 64>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
+  if (c.head_dim == 64 && c.block == 128) return launch_attn<64, 128>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
+  return RF2_ERR_UNSUPPORTED;
 }
 
 }  // namespace
@@ -527,13 +545,11 @@ int launch_attn(const rf2_plan* plan, const void* qp, const void* kp, const void
 extern "C" int rf2_block_sparse_attn(const rf2_plan* plan, const void* qp, const void* kp, const void* vp,
                                      const int32_t* blk_idx, const int32_t* blk_cnt, void* op, float* lse,
                                      void* stream) {
-  if (!plan || !qp || !kp || !vp || !blk_idx || !blk_cnt || !op) return RF2_ERR_INVALID_ARG;
-  if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
-  const rf2_config& c = plan->cfg;
-  hipStream_t st = (hipStream_t)stream;
-  if (c.head_dim == 128 && c.block == 128) return launch_attn<128, 128>(plan, qp, kp, vp, blk_idx, blk_cnt, op, lse, st);
-  if (c.head_dim == 64 && c.block == 64) return launch_attn<64, 64>(plan, qp, kp, vp, blk_idx, blk_cnt, op, lse, st);
-  if (c.head_dim == 128 && c.block == 64) return launch_attn<128, 64>(plan, qp, kp, vp, blk_idx, blk_cnt, op, lse, st);
-  if (c.head_dim == 64 && c.block == 128) return launch_attn<64, 128>(plan, qp, kp, vp, blk_idx, blk_cnt, op, lse, st);
-  return RF2_ERR_UNSUPPORTED;
+  return dispatch_attn(plan, qp, kp, vp, blk_idx, blk_cnt, op, lse, false, stream);
+}
+
+extern "C" int rf2_block_sparse_attn_unpermuted(const rf2_plan* plan, const void* qp, const void* kp, const void* vp,
+                                                const int32_t* blk_idx, const int32_t* blk_cnt, void* o, float* lse,
+                                                void* stream) {
+  return dispatch_attn(plan, qp, kp, vp, blk_idx, blk_cnt, o, lse, true, stream);
 }

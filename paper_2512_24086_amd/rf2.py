@@ -41,6 +41,7 @@ SIGNATURES = {
     "rf2_permute": (C.c_int, [C.c_void_p] * 10),
     "rf2_predict_mask": (C.c_int, [C.c_void_p] * 9),
     "rf2_block_sparse_attn": (C.c_int, [C.c_void_p] * 9),
+    "rf2_block_sparse_attn_unpermuted": (C.c_int, [C.c_void_p] * 9),
     "rf2_unpermute": (C.c_int, [C.c_void_p] * 4),
     "rf2_strerror": (C.c_char_p, [C.c_int]),
     "rf2_version": (C.c_int, []),
@@ -155,8 +156,22 @@ class Plan:
         _check(lib().rf2_block_sparse_attn(self._h, _ptr(qp), _ptr(kp), _ptr(vp), _ptr(blk_idx), _ptr(blk_cnt),
                                            _ptr(op), _ptr(lse), _stream(stream)), "rf2_block_sparse_attn")
 
+    def rf2_block_sparse_attn_unpermuted(self, qp, kp, vp, blk_idx, blk_cnt, o, lse=None, stream=None):
+        _check(lib().rf2_block_sparse_attn_unpermuted(self._h, _ptr(qp), _ptr(kp), _ptr(vp), _ptr(blk_idx),
+                                                      _ptr(blk_cnt), _ptr(o), _ptr(lse), _stream(stream)),
+               "rf2_block_sparse_attn_unpermuted")
+
     def rf2_unpermute(self, op, o, stream=None):
         _check(lib().rf2_unpermute(self._h, _ptr(op), _ptr(o), _stream(stream)), "rf2_unpermute")
+
+    def layer_fused(self, q, k, v, buf, stream=None):
+        """The whole layer with the inverse permutation fused into the attention epilogue; returns buf['o']."""
+        self.rf2_permute(q, k, v, buf["qp"], buf["kp"], buf["vp"], buf["qbar"], buf["kbar"], stream)
+        self.rf2_predict_mask(buf["qbar"], buf["kbar"], buf["blk_idx"], buf["blk_cnt"], buf.get("mask_dense"),
+                              buf.get("scores"), None, stream)
+        self.rf2_block_sparse_attn_unpermuted(buf["qp"], buf["kp"], buf["vp"], buf["blk_idx"], buf["blk_cnt"],
+                                              buf["o"], None, stream)
+        return buf["o"]
 
     def layer(self, q, k, v, buf, stream=None):
         """The whole layer, in order; returns buf['o']."""

@@ -151,3 +151,79 @@ def test_dense_layer_is_independent_of_the_permutation():
     for o in outs:
         err = np.abs(o - dense)
         assert err.max() <= hp.ATTN_MAX_ABS and err.mean() <= hp.ATTN_MEAN_ABS
+
+
+def test_fused_inverse_permutation_matches_separate_calls(case):
+    """rf2_block_sparse_attn_unpermuted == rf2_block_sparse_attn followed by rf2_unpermute, bit for bit."""
+    wl, plan, _, _, buf, _ = case
+    i = plan.info
+    o2 = torch.full_like(buf["o"], float("nan"))
+    lse2 = torch.full((wl.batch, wl.heads, i.N), float("nan"), dtype=torch.float32, device=DEV)
+    plan.rf2_block_sparse_attn_unpermuted(buf["qp"], buf["kp"], buf["vp"], buf["blk_idx"], buf["blk_cnt"], o2, lse2)
+    torch.cuda.synchronize()
+    assert torch.equal(o2.view(torch.int16), buf["o"].view(torch.int16))
+    perm, _ = plan.rf2_plan_perm()
+    want_lse = buf["lse"][:, :, :i.N].cpu().numpy()
+    got_lse = lse2.cpu().numpy()
+    assert np.array_equal(got_lse[:, :, perm], want_lse)
+
+
+def test_repeated_calls_are_bit_identical_and_streams_are_honoured():
+    """No atomics anywhere: two runs give the same bits; work goes to the stream that is passed."""
+    wl = inputs.WORKLOADS["tiny"]
+    plan = hp.make_plan(wl)
+    q, k, v = (x.to(DEV) for x in inputs.make_qkv(wl))
+    buf1, buf2 = plan.alloc(DEV), plan.alloc(DEV)
+    plan.layer(q, k, v, buf1)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plan.layer_fused(q, k, v, buf2, stream=side)
+    side.synchronize()
+    torch.cuda.synchronize()
+    for name in ("qp", "kp", "vp", "blk_idx", "blk_cnt", "o"):
+        assert torch.equal(buf1[name].view(torch.int16) if buf1[name].dtype == torch.bfloat16 else buf1[name],
+                           buf2[name].view(torch.int16) if buf2[name].dtype == torch.bfloat16 else buf2[name]), name
+    assert torch.equal(buf1["qbar"], buf2["qbar"]) and torch.equal(buf1["kbar"], buf2["kbar"])
+    plan.close()
+
+
+def test_device_calls_reject_missing_arguments():
+    wl = inputs.WORKLOADS["tiny"]
+    plan = hp.make_plan(wl)
+    buf = plan.alloc(DEV)
+    q, k, v = (x.to(DEV) for x in inputs.make_qkv(wl))
+    from paper_2512_24086_amd import rf2
+    with pytest.raises(rf2.Rf2Error) as e:
+        plan.rf2_permute(q, k, None, buf["qp"], buf["kp"], buf["vp"])
+    assert e.value.code == rf2.RF2_ERR_INVALID_ARG
+    with pytest.raises(rf2.Rf2Error):
+        plan.rf2_permute(q, k, v, buf["qp"], buf["kp"], buf["vp"], buf["qbar"], None)    # means come in pairs
+    with pytest.raises(rf2.Rf2Error):
+        plan.rf2_block_sparse_attn(buf["qp"], buf["kp"], buf["vp"], None, buf["blk_cnt"], buf["op"])
+    with pytest.raises(rf2.Rf2Error):
+        plan.rf2_block_sparse_attn_unpermuted(buf["qp"], buf["kp"], buf["vp"], buf["blk_idx"], buf["blk_cnt"], None)
+    with pytest.raises(rf2.Rf2Error):
+        plan.rf2_predict_mask(buf["qbar"], None, buf["blk_idx"], buf["blk_cnt"])
+    with pytest.raises(rf2.Rf2Error):
+        plan.rf2_unpermute(None, buf["o"])
+    plan.close()
+
+
+def test_empty_and_corrupt_lists_do_not_fault():
+    """Counts of zero give zero rows; out-of-range entries are clamped (wrong values, never a fault)."""
+    wl = inputs.WORKLOADS["tiny"]
+    plan = hp.make_plan(wl)
+    q, k, v = (x.to(DEV) for x in inputs.make_qkv(wl))
+    buf = plan.alloc(DEV, lse=True)
+    plan.layer(q, k, v, buf)
+    cnt = torch.zeros_like(buf["blk_cnt"])
+    plan.rf2_block_sparse_attn(buf["qp"], buf["kp"], buf["vp"], buf["blk_idx"], cnt, buf["op"], buf["lse"])
+    torch.cuda.synchronize()
+    assert (buf["op"].float() == 0).all() and torch.isinf(buf["lse"]).all()
+    bad = torch.full_like(buf["blk_idx"], 10 ** 6)
+    bad[..., 0] = -5
+    plan.rf2_block_sparse_attn(buf["qp"], buf["kp"], buf["vp"], bad, torch.full_like(cnt, plan.info.k_row), buf["op"])
+    torch.cuda.synchronize()
+    assert torch.isfinite(buf["op"].float()).all()
+    plan.close()
