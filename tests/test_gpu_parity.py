@@ -227,3 +227,28 @@ def test_empty_and_corrupt_lists_do_not_fault():
     torch.cuda.synchronize()
     assert torch.isfinite(buf["op"].float()).all()
     plan.close()
+
+
+@pytest.mark.parametrize("scale", [8.0, 32.0])
+def test_large_logits_take_the_reference_reset_path(scale):
+    """Logits hundreds of log2 units apart between blocks: the exponentials' reference point must be
+    re-based (overflow of a unit's row sum), and the result must still match the oracle."""
+    wl = inputs.Workload("hot", 12, 1, 2, 128, 4, 12, 16, 128, 0.4, 1, 0.3)
+    plan = hp.make_plan(wl)
+    q, k, v = inputs.make_qkv(wl)
+    q = (q.float() * scale).to(torch.bfloat16)            # exact in bf16 (power of two)
+    k = (k.float() * scale).to(torch.bfloat16)
+    buf = plan.alloc(DEV, lse=True)
+    o = plan.layer(q.to(DEV), k.to(DEV), v.to(DEV), buf)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o.float()).all()
+    for h in range(wl.heads):
+        ref = hp.oracle_layer(wl, q, k, v, h, plan)
+        M = hp.gpu_lists_to_mask(buf["blk_idx"][0, h], buf["blk_cnt"][0, h], plan.info.n_blocks)
+        want = ref["O"]
+        if not np.array_equal(M, ref["M"]):
+            Op = orc.block_sparse_attention(ref["Qp"], ref["Kp"], ref["Vp"], M, plan.cfg.block)
+            want = orc.unpermute(Op, ref["perm"])
+        err = np.abs(hp.f64(o[0, h]) - want)
+        assert err.max() <= hp.ATTN_MAX_ABS and err.mean() <= hp.ATTN_MEAN_ABS, (scale, err.max(), err.mean())
+    plan.close()
