@@ -54,6 +54,12 @@ enum {
   RF2_BUDGET_ROW_PLUS_SINK = 2  /* each row selects ceil((1-s) Tb) blocks in addition to the sink */
 };
 
+/* Memory order of the caller's q, k, v and o tensors (the paper only says Q, K, V are N x d per head). */
+enum {
+  RF2_LAYOUT_BHND = 0, /* [B, Hh, N, d]: one contiguous N x d matrix per head */
+  RF2_LAYOUT_BNHD = 1  /* [B, N, Hh, d]: token-major, heads interleaved, as many DiT code bases hold them */
+};
+
 typedef struct {
   int32_t batch, heads, head_dim; /* head_dim in {64, 128} */
   int32_t T, H, W;                /* latent grid (frames, height, width); T = 1 for an image */
@@ -64,6 +70,9 @@ typedef struct {
   int32_t sink_at_end;            /* 1: sink tokens placed after the body (Sec. 3.4, last paragraph); 0: before */
   float sparsity;                 /* target s in [0, 1) */
   int32_t budget_mode;            /* RF2_BUDGET_* */
+  int32_t qkv_layout;             /* RF2_LAYOUT_*: order of q, k, v (rf2_permute) and o (rf2_unpermute,
+                                     rf2_block_sparse_attn_unpermuted); the gathers absorb it for free.
+                                     Permuted tensors, means, lists and lse are always head-major. */
 } rf2_config;
 
 typedef struct {
@@ -101,7 +110,8 @@ int rf2_plan_perm(const rf2_plan* plan, int32_t* perm_host, int32_t* inv_host);
 
 /*
  * Sec. 3.3 permutation of Q, K, V fused with the block means of eqs. (5), (6).
- *   q, k, v : [B, Hh, N, d] bf16, tokens in [T, H, W] raster order        (in)
+ *   q, k, v : [B, Hh, N, d] (or [B, N, Hh, d], see qkv_layout) bf16, tokens in
+ *             [T, H, W] raster order                                       (in)
  *   qp      : [B, Hh, N_pad, d] bf16, qp[p] = q[perm[p]]; rows >= N zero  (out)
  *   kp      : [B, Hh, Tb, b/64, d/8, 64, 8] bf16 operand tiles.  With KH = b/2, channel
  *             8c+e of the permuted key row blk*b + r is element
@@ -166,7 +176,7 @@ int rf2_block_sparse_attn(const rf2_plan* plan, const void* qp, const void* kp, 
 /*
  * The same attention with the inverse permutation fused into its epilogue (the layer then
  * needs no rf2_unpermute and no op buffer): row p of the result goes to token perm[p].
- *   o   : [B, Hh, N, d] bf16, tokens in [T, H, W] raster order            (out)
+ *   o   : [B, Hh, N, d] (or [B, N, Hh, d], see qkv_layout) bf16, raster order (out)
  *   lse : optional [B, Hh, N] fp32, raster order, may be NULL              (out)
  * All other arguments as for rf2_block_sparse_attn; the values written are identical.
  */
@@ -174,7 +184,7 @@ int rf2_block_sparse_attn_unpermuted(const rf2_plan* plan, const void* qp, const
                                      const int32_t* blk_idx, const int32_t* blk_cnt, void* o, float* lse,
                                      void* stream);
 
-/* o[perm[p]] = op[p] for p < N.  op: [B, Hh, N_pad, d] bf16; o: [B, Hh, N, d] bf16. */
+/* o[perm[p]] = op[p] for p < N.  op: [B, Hh, N_pad, d] bf16; o: [B, Hh, N, d] (or [B, N, Hh, d]) bf16. */
 int rf2_unpermute(const rf2_plan* plan, const void* op, void* o, void* stream);
 
 /* Static description of an error code; for RF2_ERR_HIP the text of the last HIP error seen

@@ -123,7 +123,7 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
     const __bf16* __restrict__ qp, const __bf16* __restrict__ kp, const __bf16* __restrict__ vp,
     const int32_t* __restrict__ blk_idx, const int32_t* __restrict__ blk_cnt, __bf16* __restrict__ op,
     float* __restrict__ lse, const int32_t* __restrict__ row_order, int sink_per_xcd, int plain_per_xcd, int n_bh, int Tb, int k_row,
-    int last_valid, float scale_log2, const int32_t* __restrict__ scatter, int n_tokens) {
+    int last_valid, float scale_log2, const int32_t* __restrict__ scatter, int n_tokens, int heads, rf2_strides st) {
   using C = AttnCfg<D, BLK>;
   // Rings of 4 K parts (slots 0-3) and 4 V^T parts (slots 4-7); unit x uses slot x % 4 of each.
   __shared__ __attribute__((aligned(1024))) unsigned char ring[8 * C::UNIT_BYTES];
@@ -487,7 +487,8 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
       // plain output: row `row` of the permuted layout; fused inverse permutation: the token's raster row
       const int target = scatter ? scatter[row] : (int)row;
       if (target < 0) continue;                              // padding row of the last block
-      __bf16* orow = scatter ? op + ((size_t)bh * n_tokens + target) * D : op + head_off + row * D;
+      __bf16* orow = scatter ? op + ((bh / heads) * st.batch + (bh % heads) * st.head + (long long)target * st.token) * D
+                             : op + head_off + row * D;
 #pragma unroll
       for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
@@ -522,7 +523,8 @@ int launch_attn(const rf2_plan* plan, const void* qp, const void* kp, const void
                                                      blk_cnt, (__bf16*)op, lse, plan->d_row_order, plan->sink_per_xcd,
                                        plan->plain_per_xcd, n_bh,
                                                      in.n_blocks, in.k_row, in.last_block_valid, scale_log2,
-                                                     scatter ? plan->d_perm : nullptr, (int)in.N);
+                                                     scatter ? plan->d_perm : nullptr, (int)in.N, c.heads,
+                                                     rf2_qkv_strides(plan));
   RF2_LAUNCH_CHECK();
   return RF2_OK;
 }

@@ -18,6 +18,17 @@ struct rf2_plan {
   int32_t sink_per_xcd, plain_per_xcd;
 };
 
+// Strides (in rows of d elements) of the caller's q, k, v, o tensors: row of token n of head h of
+// batch b = b*batch + h*head + n*token.
+struct rf2_strides {
+  long long batch, head, token;
+};
+inline rf2_strides rf2_qkv_strides(const rf2_plan* p) {
+  const long long N = p->info.N, Hh = p->cfg.heads;
+  if (p->cfg.qkv_layout == RF2_LAYOUT_BNHD) return {N * Hh, 1, Hh};
+  return {Hh * N, N, 1};
+}
+
 // Remembers the text of a failed HIP call for rf2_strerror (per calling thread).
 int rf2_note_hip_error(hipError_t e);
 

@@ -21,12 +21,12 @@ template <int D, int BLK>
 __global__ void __launch_bounds__(256) permute_pool_kernel(
     const uint4* __restrict__ q, const uint4* __restrict__ k, uint4* __restrict__ qp, uint4* __restrict__ kp,
     float* __restrict__ qbar, float* __restrict__ kbar, const int32_t* __restrict__ perm,
-    int N, int n_blocks, int last_valid) {
+    int N, int n_blocks, int last_valid, int heads, rf2_strides st) {
   constexpr int CH = D / 8;          // 16-byte chunks per row
   constexpr int RG = 256 / CH;       // rows moved per pass
   const int blk = blockIdx.x;
   const int bh = blockIdx.y;
-  const uint4* __restrict__ src = (blockIdx.z == 0 ? q : k) + (size_t)bh * N * CH;
+  const uint4* __restrict__ src = (blockIdx.z == 0 ? q : k) + ((bh / heads) * st.batch + (bh % heads) * st.head) * CH;
   uint4* __restrict__ dst = (blockIdx.z == 0 ? qp : kp) + ((size_t)bh * n_blocks + blk) * BLK * CH;
   float* __restrict__ mean = blockIdx.z == 0 ? qbar : kbar;
   const int c = threadIdx.x % CH, rg = threadIdx.x / CH;
@@ -36,7 +36,7 @@ __global__ void __launch_bounds__(256) permute_pool_kernel(
   for (int r = rg; r < BLK; r += RG) {
     const int n = perm[blk * BLK + r];
     uint4 x = make_uint4(0u, 0u, 0u, 0u);
-    if (n >= 0) x = src[(size_t)n * CH + c];
+    if (n >= 0) x = src[(size_t)n * st.token * CH + c];
     constexpr int KH = BLK / 2;
     const int kslot = ((r % KH) / 32 * CH + c) * 64 + (r / KH) * 32 + r % 32;
     dst[blockIdx.z == 0 ? r * CH + c : kslot] = x;
@@ -70,18 +70,19 @@ __device__ __forceinline__ int rho(int r) { return (r & 3) | ((r & 4) << 1) | ((
 // channel ch of those 8 keys.
 template <int D, int BLK>
 __global__ void __launch_bounds__(256) permute_vtile_kernel(
-    const uint4* __restrict__ v, uint4* __restrict__ vp, const int32_t* __restrict__ perm, int N, int n_blocks) {
+    const uint4* __restrict__ v, uint4* __restrict__ vp, const int32_t* __restrict__ perm, int N, int n_blocks,
+    int heads, rf2_strides st) {
   constexpr int CH = D / 8;
   constexpr int RG = 256 / CH;
   constexpr int PITCH = D + 2;       // u16 elements per LDS row: odd number of dwords
   __shared__ __attribute__((aligned(16))) u16 tile[BLK * PITCH];
   const int blk = blockIdx.x, bh = blockIdx.y;
-  const uint4* __restrict__ src = v + (size_t)bh * N * CH;
+  const uint4* __restrict__ src = v + ((bh / heads) * st.batch + (bh % heads) * st.head) * CH;
   const int c = threadIdx.x % CH, rg = threadIdx.x / CH;
   for (int r = rg; r < BLK; r += RG) {
     const int n = perm[blk * BLK + r];
     uint4 x = make_uint4(0u, 0u, 0u, 0u);
-    if (n >= 0) x = src[(size_t)n * CH + c];
+    if (n >= 0) x = src[(size_t)n * st.token * CH + c];
     uint32_t* row = reinterpret_cast<uint32_t*>(tile + r * PITCH + c * 8);  // 4-byte aligned: PITCH, c*8 even
     row[0] = x.x; row[1] = x.y; row[2] = x.z; row[3] = x.w;
   }
@@ -107,18 +108,19 @@ __global__ void __launch_bounds__(256) permute_vtile_kernel(
 // o[n] = op[inv[n]]: gathered reads, fully sequential writes.
 template <int D>
 __global__ void __launch_bounds__(256) unpermute_kernel(
-    const uint4* __restrict__ op, uint4* __restrict__ o, const int32_t* __restrict__ inv, int N, size_t N_pad) {
+    const uint4* __restrict__ op, uint4* __restrict__ o, const int32_t* __restrict__ inv, int N, size_t N_pad,
+    int heads, rf2_strides st) {
   constexpr int CH = D / 8;
   constexpr int RG = 256 / CH;
   const int bh = blockIdx.y;
   const uint4* __restrict__ src = op + (size_t)bh * N_pad * CH;
-  uint4* __restrict__ dst = o + (size_t)bh * N * CH;
+  uint4* __restrict__ dst = o + ((bh / heads) * st.batch + (bh % heads) * st.head) * CH;
   const int c = threadIdx.x % CH, rg = threadIdx.x / CH;
   const int n0 = blockIdx.x * 128;
 #pragma unroll 4
   for (int r = rg; r < 128; r += RG) {
     const int n = n0 + r;
-    if (n < N) dst[(size_t)n * CH + c] = src[(size_t)inv[n] * CH + c];
+    if (n < N) dst[(size_t)n * st.token * CH + c] = src[(size_t)inv[n] * CH + c];
   }
 }
 
@@ -133,14 +135,15 @@ extern "C" int rf2_permute(const rf2_plan* plan, const void* q, const void* k, c
   const rf2_info& in = plan->info;
   hipStream_t st = (hipStream_t)stream;
   const dim3 grid_qk(in.n_blocks, c.batch * c.heads, 2), grid_v(in.n_blocks, c.batch * c.heads, 1);
+  const rf2_strides strides = rf2_qkv_strides(plan);
 #define RF2_PERMUTE_CASE(DD, BB)                                                                              \
   if (c.head_dim == DD && c.block == BB) {                                                                    \
     permute_pool_kernel<DD, BB><<<grid_qk, 256, 0, st>>>((const uint4*)q, (const uint4*)k, (uint4*)qp,        \
                                                           (uint4*)kp, qbar, kbar, plan->d_perm, (int)in.N,     \
-                                                          in.n_blocks, in.last_block_valid);                   \
+                                                          in.n_blocks, in.last_block_valid, c.heads, strides);  \
     RF2_LAUNCH_CHECK();                                                                                       \
     permute_vtile_kernel<DD, BB><<<grid_v, 256, 0, st>>>((const uint4*)v, (uint4*)vp, plan->d_perm, (int)in.N, \
-                                                          in.n_blocks);                                        \
+                                                          in.n_blocks, c.heads, strides);                      \
     RF2_LAUNCH_CHECK();                                                                                       \
     return RF2_OK;                                                                                            \
   }
@@ -160,9 +163,11 @@ extern "C" int rf2_unpermute(const rf2_plan* plan, const void* op, void* o, void
   hipStream_t st = (hipStream_t)stream;
   const dim3 grid((unsigned)((in.N + 127) / 128), c.batch * c.heads, 1);
   if (c.head_dim == 128)
-    unpermute_kernel<128><<<grid, 256, 0, st>>>((const uint4*)op, (uint4*)o, plan->d_inv, (int)in.N, (size_t)in.N_pad);
+    unpermute_kernel<128><<<grid, 256, 0, st>>>((const uint4*)op, (uint4*)o, plan->d_inv, (int)in.N, (size_t)in.N_pad,
+                                         c.heads, rf2_qkv_strides(plan));
   else
-    unpermute_kernel<64><<<grid, 256, 0, st>>>((const uint4*)op, (uint4*)o, plan->d_inv, (int)in.N, (size_t)in.N_pad);
+    unpermute_kernel<64><<<grid, 256, 0, st>>>((const uint4*)op, (uint4*)o, plan->d_inv, (int)in.N, (size_t)in.N_pad,
+                                         c.heads, rf2_qkv_strides(plan));
   RF2_LAUNCH_CHECK();
   return RF2_OK;
 }

@@ -71,6 +71,7 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
   if (c.sink_at_end != 0 && c.sink_at_end != 1) return RF2_ERR_INVALID_ARG;
   if (!(c.sparsity >= 0.0f && c.sparsity < 1.0f)) return RF2_ERR_INVALID_ARG;  // also rejects NaN
   if (c.budget_mode < RF2_BUDGET_GLOBAL || c.budget_mode > RF2_BUDGET_ROW_PLUS_SINK) return RF2_ERR_INVALID_ARG;
+  if (c.qkv_layout != RF2_LAYOUT_BHND && c.qkv_layout != RF2_LAYOUT_BNHD) return RF2_ERR_INVALID_ARG;
   if (c.wt < 0 || c.wh < 0 || c.ww < 0) return RF2_ERR_INVALID_ARG;
   const bool win_default = (c.wt == 0 && c.wh == 0 && c.ww == 0);
   if (!win_default && (c.wt < 1 || c.wh < 1 || c.ww < 1)) return RF2_ERR_INVALID_ARG;

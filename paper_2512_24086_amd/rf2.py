@@ -16,12 +16,13 @@ LIB_PATH = os.path.join(_PKG, "librf2.so")
 RF2_OK = 0
 RF2_ERR_INVALID_ARG, RF2_ERR_UNSUPPORTED, RF2_ERR_ALLOC, RF2_ERR_HIP = -1, -2, -3, -4
 RF2_BUDGET_GLOBAL, RF2_BUDGET_ROW_INCL_SINK, RF2_BUDGET_ROW_PLUS_SINK = 0, 1, 2
+RF2_LAYOUT_BHND, RF2_LAYOUT_BNHD = 0, 1
 
 
 class rf2_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "heads", "head_dim", "T", "H", "W", "wt", "wh", "ww",
                                          "block", "sink_frames", "sink_at_end")] + \
-               [("sparsity", C.c_float), ("budget_mode", C.c_int32)]
+               [("sparsity", C.c_float), ("budget_mode", C.c_int32), ("qkv_layout", C.c_int32)]
 
 
 class rf2_info(C.Structure):
@@ -92,9 +93,9 @@ class Plan:
     """Owner of an rf2_plan*; methods carry the names of the C entry points."""
 
     def __init__(self, *, batch, heads, head_dim, T, H, W, block, sparsity, sink_frames=0, sink_at_end=1,
-                 window=(0, 0, 0), budget_mode=RF2_BUDGET_GLOBAL):
+                 window=(0, 0, 0), budget_mode=RF2_BUDGET_GLOBAL, qkv_layout=RF2_LAYOUT_BHND):
         self.cfg = rf2_config(batch, heads, head_dim, T, H, W, window[0], window[1], window[2], block,
-                              sink_frames, int(sink_at_end), float(sparsity), budget_mode)
+                              sink_frames, int(sink_at_end), float(sparsity), budget_mode, qkv_layout)
         self._h = C.c_void_p(0)
         _check(lib().rf2_plan_create(C.byref(self.cfg), C.byref(self._h)), "rf2_plan_create")
         self.info = rf2_info()
@@ -132,7 +133,9 @@ class Plan:
             kbar=torch.empty(*bh, i.n_blocks, c.head_dim, dtype=torch.float32, device=device),
             blk_idx=torch.empty(*bh, i.n_blocks, i.k_row, dtype=torch.int32, device=device),
             blk_cnt=torch.empty(*bh, i.n_blocks, dtype=torch.int32, device=device),
-            op=torch.empty(*bh, i.N_pad, c.head_dim, **bf), o=torch.empty(*bh, i.N, c.head_dim, **bf))
+            op=torch.empty(*bh, i.N_pad, c.head_dim, **bf),
+            o=(torch.empty(c.batch, i.N, c.heads, c.head_dim, **bf) if c.qkv_layout == RF2_LAYOUT_BNHD
+               else torch.empty(*bh, i.N, c.head_dim, **bf)))
         if dense_mask:
             buf["mask_dense"] = torch.empty(*bh, i.n_blocks, i.n_blocks, dtype=torch.uint8, device=device)
         if scores:

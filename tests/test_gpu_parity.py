@@ -252,3 +252,31 @@ def test_large_logits_take_the_reference_reset_path(scale):
         err = np.abs(hp.f64(o[0, h]) - want)
         assert err.max() <= hp.ATTN_MAX_ABS and err.mean() <= hp.ATTN_MEAN_ABS, (scale, err.max(), err.mean())
     plan.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "ragged_d128_b128"])
+def test_token_major_layout_gives_identical_results(name):
+    """q, k, v, o held as [B, N, Hh, d]: every intermediate and the output are bit-identical to the
+    head-major run (the layout only changes the addresses of the gathers and of the final scatter)."""
+    from paper_2512_24086_amd import rf2
+    wl, over = SMALL[name]
+    q, k, v = (x.to(DEV) for x in inputs.make_qkv(wl))
+    plan_a = hp.make_plan(wl, **over)
+    plan_b = hp.make_plan(wl, qkv_layout=rf2.RF2_LAYOUT_BNHD, **over)
+    buf_a, buf_b = plan_a.alloc(DEV), plan_b.alloc(DEV)
+    qt, kt, vt = (x.transpose(1, 2).contiguous() for x in (q, k, v))
+    plan_a.layer(q, k, v, buf_a)
+    plan_b.layer(qt, kt, vt, buf_b)
+    torch.cuda.synchronize()
+    assert buf_b["o"].shape == (wl.batch, wl.N, wl.heads, wl.head_dim)
+    for n in ("qp", "kp", "vp", "op"):
+        assert torch.equal(buf_a[n].view(torch.int16), buf_b[n].view(torch.int16)), n
+    assert torch.equal(buf_a["qbar"], buf_b["qbar"]) and torch.equal(buf_a["blk_idx"], buf_b["blk_idx"])
+    assert torch.equal(buf_a["o"].view(torch.int16), buf_b["o"].transpose(1, 2).contiguous().view(torch.int16))
+    o_fused = torch.full_like(buf_b["o"], float("nan"))
+    plan_b.rf2_block_sparse_attn_unpermuted(buf_b["qp"], buf_b["kp"], buf_b["vp"], buf_b["blk_idx"], buf_b["blk_cnt"],
+                                            o_fused)
+    torch.cuda.synchronize()
+    assert torch.equal(o_fused.view(torch.int16), buf_b["o"].view(torch.int16))
+    plan_a.close()
+    plan_b.close()

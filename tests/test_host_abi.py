@@ -39,7 +39,7 @@ def make_plan(**kw):
 @pytest.mark.parametrize("bad", [
     dict(batch=0), dict(heads=0), dict(T=0), dict(sink_frames=6), dict(sink_frames=-1), dict(sparsity=1.0),
     dict(sparsity=-0.1), dict(sparsity=float("nan")), dict(budget_mode=3), dict(window=(0, 4, 4)),
-    dict(window=(-1, 4, 4)), dict(sink_at_end=2),
+    dict(window=(-1, 4, 4)), dict(sink_at_end=2), dict(qkv_layout=2), dict(qkv_layout=-1),
 ])
 def test_invalid_configs_are_rejected(bad):
     with pytest.raises(rf2.Rf2Error) as e:
