@@ -26,6 +26,8 @@
 // steps ahead of their use, with one barrier per step.
 #include "rf2_internal.h"
 
+#include <type_traits>
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -509,13 +511,360 @@ __global__ void __launch_bounds__(BLK * 2) block_sparse_attn_kernel(
   }
 }
 
+
+// ======================================================================================
+// Variant X: 32 query rows per wavefront, every wavefront walks all keys, two workgroups
+// per compute unit (two wavefronts per SIMD).
+// ======================================================================================
+#ifndef X_OCC
+#define X_OCC 2
+#endif
+#ifndef X_PD
+#define X_PD 4
+#endif
+#ifndef X_FREEZE
+#define X_FREEZE 1
+#endif
+#ifndef X_NOSOFTMAX
+#define X_NOSOFTMAX 0
+#endif
+#ifndef X_ORDER
+#define X_ORDER 0
+#endif
+#ifndef X_NOLDS
+#define X_NOLDS 0
+#endif
+#ifndef X_DMASAME
+#define X_DMASAME 0
+#endif
+#ifndef X_PVASM
+#define X_PVASM 0
+#endif
+#ifndef X_NODMA
+#define X_NODMA 0
+#endif
+template <int D, int BLK>
+struct XCfg {
+  static constexpr int NW = BLK / 32;           // wavefronts, 32 query rows each
+  static constexpr int NT = NW * 64;
+  static constexpr int KH = BLK / 2;
+  static constexpr int PB = BLK / 64;           // 64-key parts per block
+  static constexpr int UB = BLK / 32;           // 32-key units per block
+  static constexpr int DS = D / 16;
+  static constexpr int DT = D / 32;
+  static constexpr int TILE_BYTES = BLK * D * 2;
+  static constexpr int PART_BYTES = 64 * D * 2;
+  static constexpr int LPW = PART_BYTES / 1024 / NW;   // 1 KiB loads per wavefront per part
+  static constexpr int NK = 3, NV = 2;                 // ring depths in parts
+  static_assert(LPW >= 1 && 2 * LPW < 63, "vmcnt range");
+};
+
+// O^T += A * B with the accumulator tile held in the accumulation register file.
+__device__ __forceinline__ void pv_acc(f32x16& O, const bf16x8& a, const bf16x8& b) {
+#if X_PVASM
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(O) : "v"(a), "v"(b));
+#else
+  O = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, O, 0, 0, 0);
+#endif
+}
+__device__ __forceinline__ void qk_last1(f32x16& S0, const bf16x8& a, const bf16x8& b0) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\t"
+      "s_nop 7\n\ts_nop 7\n\ts_nop 1"
+      : "+v"(S0)
+      : "v"(a), "v"(b0));
+}
+
+template <int D, int BLK>
+__global__ void __launch_bounds__(BLK * 2, X_OCC) block_sparse_attn_kernel_x(
+    const __bf16* __restrict__ qp, const __bf16* __restrict__ kp, const __bf16* __restrict__ vp,
+    const int32_t* __restrict__ blk_idx, const int32_t* __restrict__ blk_cnt, __bf16* __restrict__ op,
+    float* __restrict__ lse, const int32_t* __restrict__ row_order, int sink_per_xcd, int plain_per_xcd, int n_bh, int Tb, int k_row,
+    int last_valid, float scale_log2, const int32_t* __restrict__ scatter, int n_tokens, int heads, rf2_strides st) {
+  using C = XCfg<D, BLK>;
+  __shared__ __attribute__((aligned(1024))) unsigned char ring[(C::NK + C::NV) * C::PART_BYTES];
+  constexpr uint32_t VRING = C::NK * C::PART_BYTES;
+
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int lead = min(2, n_bh), both = sink_per_xcd + plain_per_xcd;
+  int bh, entry;
+  if (slot < lead * sink_per_xcd) {
+    bh = slot / sink_per_xcd;
+    entry = slot % sink_per_xcd;
+  } else {
+    const int t = slot - lead * sink_per_xcd;
+    if (t < (n_bh - lead) * both) {
+      const int ph = t / both, r = t % both;
+      bh = r < sink_per_xcd ? ph + lead : ph;
+      entry = r;
+    } else {
+      const int u = t - (n_bh - lead) * both;
+      bh = n_bh - lead + u / plain_per_xcd;
+      entry = sink_per_xcd + u % plain_per_xcd;
+    }
+  }
+  const int qi = row_order[xcd * (sink_per_xcd + plain_per_xcd) + entry];
+  if (qi < 0) return;
+  const size_t row_id = (size_t)bh * Tb + qi;
+  int cnt = blk_cnt[row_id];
+  const bool dense = (cnt == Tb);
+  cnt = dense ? Tb : min(max(cnt, 0), k_row);
+  const int32_t* __restrict__ list = blk_idx + row_id * k_row;
+  const int U = cnt * C::UB;                            // 32-key units to process (even)
+  const int NPARTS = cnt * C::PB;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t tid16 = (uint32_t)tid * 16u;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const size_t head_off = (size_t)bh * Tb * BLK * D;
+  const unsigned char* const kbase = uniform_ptr(kp + head_off);
+  const unsigned char* const vbase = uniform_ptr(vp + head_off);
+  // LDS byte offsets of this lane's first operand chunk inside a K part / a V^T part (tile 0)
+  const uint32_t k_lane = (uint32_t)((lh * 64 + l32) * 16);
+  const uint32_t v_lane = (uint32_t)((lh * D + l32) * 16);
+  constexpr uint32_t K_TILE = 32 * 16, V_TILE = 4 * D * 16;   // offset of tile 1 inside a part
+  auto list_entry = [&](int P) {
+    const int it = min(P, NPARTS - 1) / C::PB;
+    return dense ? it : list[it];
+  };
+  auto part_off = [&](int entry, int P) {
+    const int j = min(max(entry, 0), Tb - 1);            // a corrupt list can give wrong results, never a fault
+    return (uint32_t)j * (uint32_t)C::TILE_BYTES + (uint32_t)(min(P, NPARTS - 1) % C::PB) * (uint32_t)C::PART_BYTES;
+  };
+  auto part_at = [&](int P) { return (size_t)part_off(list_entry(P), P); };
+  const uint32_t ring_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)ring;
+  int partial_begin = U;
+  if (U > 0 && last_valid < BLK) {
+    const int jl = dense ? cnt - 1 : list[cnt - 1];
+    if (min(max(jl, 0), Tb - 1) == Tb - 1) partial_begin = (cnt - 1) * C::UB;
+  }
+
+  bf16x8 qf[C::DS];
+  f32x16 o[C::DT];
+#pragma unroll
+  for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  constexpr int NQ = C::DS, NP = C::DT * 2, NSLOT = NQ + NP;
+  constexpr int PD = X_PD;
+  constexpr int SPP = NSLOT / 8;                         // slots per softmax pair (8 pairs per unit)
+  static_assert(NSLOT % 8 == 0 && NQ >= 2 && 2 * C::LPW <= NSLOT, "slot plan");
+  // Slot g of a step is the QK k-step qk_of(g) (if >= 0) or the PV product (dt, ks) = pv_of(g).
+  // X_ORDER 0: all QK slots, then PV slots pairwise per channel tile; 1: QK and PV alternate and
+  // consecutive PV products go to different accumulators (no MFMA depends on its predecessor).
+  auto qk_of = [](int g) { return X_ORDER ? ((g & 1) ? -1 : g / 2) : (g < NQ ? g : -1); };
+  auto pv_dt = [](int g) { return X_ORDER ? (g / 2) % C::DT : (g - NQ) / 2; };
+  auto pv_ks = [](int g) { return X_ORDER ? (g / 2) / C::DT : (g - NQ) % 2; };
+  auto k_operand = [&](uint32_t k_addr, int c) -> bf16x8 {
+    return *reinterpret_cast<const bf16x8*>(ring + k_addr + c * 2048);
+  };
+  auto v_operand = [&](uint32_t v_addr, int dt, int ks) -> bf16x8 {
+    return *reinterpret_cast<const bf16x8*>(ring + v_addr + (2 * ks * D + 32 * dt) * 16);
+  };
+  auto operand = [&](uint32_t k_addr, uint32_t v_addr, int g) -> bf16x8 {
+    return qk_of(g) >= 0 ? k_operand(k_addr, qk_of(g)) : v_operand(v_addr, pv_dt(g), pv_ks(g));
+  };
+  auto rowmax = [&](const f32x16& S) -> float {
+    float v = S[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) v = fmaxf(v, S[i]);
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * scale_log2;
+  };
+  auto need_slow = [&](float mx, int s) {
+    const bool raise = mx > m_run + 8.0f;
+    return (__builtin_amdgcn_ballot_w64(raise) != 0ull) || (s >= partial_begin);
+  };
+  auto slow_path = [&](f32x16& S, float& mx, bf16x8 (&Pprev)[2], uint32_t v_addr, int s) {
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+      const int dt = j % C::DT, ks = j / C::DT;
+      pv_acc(o[dt], v_operand(v_addr, dt, ks), Pprev[ks]);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) Pprev[ks][e] = (__bf16)0.f;
+    if (s >= partial_begin) {
+      const int t = s & 1, p = (s >> 1) % C::PB;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = t * C::KH + 32 * p + 8 * (i / 4) + 4 * lh + (i % 4);
+        if (key >= last_valid) S[i] = -INFINITY;
+      }
+      mx = rowmax(S);
+    }
+    const bool raise = mx > m_run + 8.0f;
+    if (__builtin_amdgcn_ballot_w64(raise) != 0ull) {
+      const float alpha = raise ? __builtin_amdgcn_exp2f(m_run - mx) : 1.0f;
+      m_run = raise ? mx : m_run;
+      l_run *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;
+    }
+  };
+
+  int entry_k = 0, entry_v = 0;       // list entries of the parts loaded by the next odd step
+  bool slow = true;
+  // Step s (unit s = tile s%2 of part s/2): products S_{s+1} and V P_{s-1} around the softmax
+  // arithmetic of unit s.  Part P lives in slot P % NK of the K ring and P % NV of the V ring.
+  // Odd steps s = 2P+1 start with the barrier and issue the loads of V part P+1 and K part P+3.
+  auto step = [&](auto odd_tag, int s, int kslot, int vslot, int kfree, int vfree, f32x16& Scur, f32x16& Snext,
+                  bf16x8 (&Pprev)[2], bf16x8 (&Pcur)[2], float& mxcur, float& mxnext) {
+    constexpr bool ODD = decltype(odd_tag)::value;
+    if constexpr (ODD) ring_barrier<C::LPW>();
+    // unit s+1 and unit s-1 are both tile (s+1)%2 = ODD ? 0 : 1
+    const uint32_t k_addr = (uint32_t)(kslot * C::PART_BYTES) + (ODD ? 0u : K_TILE) + k_lane;
+    const uint32_t v_addr = VRING + (uint32_t)(vslot * C::PART_BYTES) + (ODD ? 0u : V_TILE) + v_lane;
+    if (slow) slow_path(Scur, mxcur, Pprev, v_addr, s);
+    uint32_t k_dst = 0, v_dst = 0, k_voff = 0, v_voff = 0;
+    if constexpr (ODD) {
+      const int P = s >> 1;
+      k_dst = ring_lds + (uint32_t)(kfree * C::PART_BYTES + wave * 1024);
+      v_dst = ring_lds + VRING + (uint32_t)(vfree * C::PART_BYTES + wave * 1024);
+      k_voff = tid16 + (X_DMASAME ? 0u : part_off(entry_k, P + 3));
+      v_voff = tid16 + (X_DMASAME ? 0u : part_off(entry_v, P + 1));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+    float rs = 0.f;
+    bf16x8 opnd[NSLOT];
+#pragma unroll
+    for (int g = 0; g < PD; ++g) opnd[g] = operand(k_addr, v_addr, g);
+    if constexpr (ODD) {
+      const int P = s >> 1;
+      entry_k = list_entry(P + 4);   // for the next odd step
+      entry_v = list_entry(P + 2);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int g = 0; g < NSLOT; ++g) {
+      if (g + PD < NSLOT && !X_NOLDS) opnd[g + PD] = operand(k_addr, v_addr, g + PD);
+      {
+        const int c = qk_of(g);
+        if (c == 0) qk_first(Snext, opnd[g], qf[0]);
+        else if (c > 0 && c < NQ - 1) qk_next(Snext, opnd[g], qf[c]);
+        else if (c == NQ - 1) qk_last1(Snext, opnd[g], qf[c]);
+        else pv_acc(o[pv_dt(g)], opnd[g], Pprev[pv_ks(g)]);
+      }
+      if (g % SPP == 0 && !X_NOSOFTMAX) {
+        const int i = 2 * (g / SPP);
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[i], scale_log2, -m_use));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(Scur[i + 1], scale_log2, -m_use));
+        const bf16x2 pk = {(__bf16)p0, (__bf16)p1};
+        rs += p0 + p1;
+        Pcur[i / 8][i % 8] = pk[0];
+        Pcur[i / 8][i % 8 + 1] = pk[1];
+      }
+      if constexpr (ODD && !X_NODMA) {
+        // V^T part first, K part second: the barrier of the next odd step then waits for all but the K loads
+        if (g < C::LPW) dma_one(v_dst + g * (C::NW * 1024), vbase + g * (C::NW * 1024), v_voff);
+        else if (g < 2 * C::LPW) dma_one(k_dst + (g - C::LPW) * (C::NW * 1024), kbase + (g - C::LPW) * (C::NW * 1024), k_voff);
+      }
+      if (!X_ORDER && g == NQ + 1) mxnext = rowmax(Snext);
+      if (X_FREEZE) __builtin_amdgcn_sched_barrier(0);
+    }
+    if (X_ORDER) mxnext = rowmax(Snext);
+    asm volatile("" : "+v"(Pcur[0]), "+v"(Pcur[1]), "+v"(rs));
+    l_run += rs;
+    slow = need_slow(mxnext, s + 1);
+  };
+
+  if (U > 0) {
+    // ---- prologue: K parts 0..2, V^T part 0 (and a finite stand-in for "part -1"), Q, S of unit 0 ----
+    dma_unit<C::NW, C::LPW>(ring + 0 * C::PART_BYTES, kbase + part_at(0), wave, tid16);
+    dma_unit<C::NW, C::LPW>(ring + VRING + 0 * C::PART_BYTES, vbase + part_at(0), wave, tid16);
+    dma_unit<C::NW, C::LPW>(ring + 1 * C::PART_BYTES, kbase + part_at(1), wave, tid16);
+    dma_unit<C::NW, C::LPW>(ring + 2 * C::PART_BYTES, kbase + part_at(2), wave, tid16);
+    dma_unit<C::NW, C::LPW>(ring + VRING + 1 * C::PART_BYTES, vbase + part_at(0), wave, tid16);
+    {
+      const __bf16* qrow = qp + head_off + ((size_t)qi * BLK + 32 * wave + l32) * D + 8 * lh;
+#pragma unroll
+      for (int ds = 0; ds < C::DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ds);
+    }
+    f32x16 Sa, Sb;
+    bf16x8 Pa[2], Pb[2];
+    float mxa, mxb = 0.f;
+    ring_barrier<0>();
+#pragma unroll
+    for (int ds = 0; ds < C::DS; ++ds) {
+      const bf16x8 a = k_operand(k_lane, ds);
+      if (ds == 0) qk_first(Sa, a, qf[ds]);
+      else if (ds < C::DS - 1) qk_next(Sa, a, qf[ds]);
+      else qk_last1(Sa, a, qf[ds]);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) Pb[ks][e] = (__bf16)0.f;
+    mxa = rowmax(Sa);
+    slow = true;
+    entry_k = list_entry(3);
+    entry_v = list_entry(1);
+
+    // ---- steady state: two steps per part ---------------------------------------------------
+    int k0 = 0, k1 = 1;                                   // K ring slots of parts P and P+1
+    for (int s = 0; s < U; s += 2) {
+      const int P = s >> 1;
+      // even step: S of unit s+1 (part P, tile 1), V P of unit s-1 (part P-1, tile 1)
+      step(std::false_type{}, s, k0, (P + 1) & 1, 0, 0, Sa, Sb, Pb, Pa, mxa, mxb);
+      // odd step: S of unit s+2 (part P+1, tile 0), V P of unit s (part P, tile 0);
+      // loads K part P+3 into the slot of part P and V^T part P+1 into the slot of part P-1
+      step(std::true_type{}, s + 1, k1, P & 1, k0, (P + 1) & 1, Sb, Sa, Pa, Pb, mxb, mxa);
+      k0 = k1;
+      k1 = (k1 == C::NK - 1) ? 0 : k1 + 1;
+    }
+    // ---- last product: O += V P_{U-1} (part U/2-1, tile 1; P_{U-1} is in Pb) ----------------------
+    ring_barrier<0>();
+    {
+      const int P = (U >> 1) - 1;
+      const uint32_t v_addr = VRING + (uint32_t)((P & 1) * C::PART_BYTES) + V_TILE + v_lane;
+#pragma unroll
+      for (int j = 0; j < NP; ++j) {
+        const int dt = j % C::DT, ks = j / C::DT;
+        pv_acc(o[dt], v_operand(v_addr, dt, ks), Pb[ks]);
+      }
+    }
+  }
+
+  // ---- normalise (eq. 4's final division) and write the 32 rows of this wavefront --------------
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
+  const float l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+  const float f = l_tot > 0.f ? 1.0f / l_tot : 0.f;      // a row with no kept key yields zeros
+  const size_t row = (size_t)qi * BLK + 32 * wave + l32;
+  const int target = scatter ? scatter[row] : (int)row;
+  if (target < 0) return;                                 // padding row of the last block
+  __bf16* orow = scatter ? op + ((bh / heads) * st.batch + (bh % heads) * st.head + (long long)target * st.token) * D
+                         : op + head_off + row * D;
+#pragma unroll
+  for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 pk;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(o[dt][4 * g + e] * f);
+      *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g + 4 * lh) = pk;
+    }
+  if (lse != nullptr && lh == 0)
+    lse[scatter ? (size_t)bh * n_tokens + target : (size_t)bh * Tb * BLK + row] =
+        m_run * 0.6931471805599453f + __logf(l_tot);
+}
+
 template <int D, int BLK>
 int launch_attn(const rf2_plan* plan, const void* qp, const void* kp, const void* vp, const int32_t* blk_idx,
                 const int32_t* blk_cnt, void* op, float* lse, bool scatter, hipStream_t st) {
   using C = AttnCfg<D, BLK>;
   const rf2_config& c = plan->cfg;
   const rf2_info& in = plan->info;
+#ifdef RF2_ATTN_X
+  auto kern = block_sparse_attn_kernel_x<D, BLK>;
+#else
   auto kern = block_sparse_attn_kernel<D, BLK>;
+#endif
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
   const int n_bh = c.batch * c.heads;
   const unsigned grid = 8u * (unsigned)(plan->sink_per_xcd + plan->plain_per_xcd) * (unsigned)n_bh;
