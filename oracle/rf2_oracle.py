@@ -70,17 +70,31 @@ def _window_order(frames: np.ndarray, H: int, W: int, wt: int, wh: int, ww: int)
 
 
 def perm_table(T: int, H: int, W: int, wt: int, wh: int, ww: int,
-               sink_frames: int = 0, sink_at_end: bool = True) -> np.ndarray:
-    """perm[p] = raster index n=(t*H+h)*W+w of the token placed at permuted
-    position p.  Body frames (t >= sink_frames) use 3-D windows (wt,wh,ww);
-    sink frames use 2-D windows (1,wh,ww) frame by frame and are placed after
-    the body (Sec. 3.4, last paragraph) or before it (Fig. 1)."""
+               sink_frames: int = 0, sink_at_end: bool = True, text_tokens: int = 0) -> np.ndarray:
+    """perm[p] = input index of the token placed at permuted position p.  The
+    input lists the video tokens in raster order n=(t*H+h)*W+w, then
+    `text_tokens` tokens of the other modality.  Body frames (t >= sink_frames)
+    use 3-D windows (wt,wh,ww); sink frames use 2-D windows (1,wh,ww) frame by
+    frame and are placed after the body (Sec. 3.4, last paragraph) or before it
+    (Fig. 1).  Text tokens keep their order and come last, next to the sink
+    frame (Sec. 3.4, last paragraph: both take part in full attention)."""
+    _check_tail(sink_frames, sink_at_end, text_tokens)
     body = _window_order(np.arange(sink_frames, T), H, W, wt, wh, ww)
-    if sink_frames == 0:
-        return body.astype(np.int64)
-    sink = _window_order(np.arange(0, sink_frames), H, W, 1, wh, ww)
-    parts = (body, sink) if sink_at_end else (sink, body)
+    parts = [body]
+    if sink_frames > 0:
+        sink = _window_order(np.arange(0, sink_frames), H, W, 1, wh, ww)
+        parts = [body, sink] if sink_at_end else [sink, body]
+    parts.append(T * H * W + np.arange(text_tokens))
     return np.concatenate(parts).astype(np.int64)
+
+
+def _check_tail(sink_frames: int, sink_at_end: bool, text_tokens: int) -> None:
+    """The always-dense tokens (sink frames, text) must form ONE run of the
+    permuted sequence; a sink at the front plus text at the end would be two."""
+    if text_tokens < 0:
+        raise ValueError("text_tokens must be >= 0")
+    if text_tokens > 0 and sink_frames > 0 and not sink_at_end:
+        raise ValueError("text tokens need the sink frames at the end of the sequence")
 
 
 def inverse_table(perm: np.ndarray) -> np.ndarray:
@@ -113,14 +127,16 @@ def block_slice(i: int, N: int, b: int) -> slice:
 
 
 def sink_block_range(N: int, frame_tokens: int, b: int, sink_frames: int,
-                     sink_at_end: bool = True) -> tuple[int, int]:
-    """[begin, end) of the blocks that hold at least one sink-frame token."""
+                     sink_at_end: bool = True, text_tokens: int = 0) -> tuple[int, int]:
+    """[begin, end) of the blocks that hold at least one always-dense token: a
+    sink-frame token or a text token (N counts the text tokens too)."""
+    _check_tail(sink_frames, sink_at_end, text_tokens)
     n_sink = sink_frames * frame_tokens
     Tb = n_blocks(N, b)
-    if n_sink == 0:
+    if n_sink + text_tokens == 0:
         return (0, 0)
-    if sink_at_end:
-        return ((N - n_sink) // b, Tb)
+    if sink_at_end or n_sink == 0:
+        return ((N - n_sink - text_tokens) // b, Tb)
     return (0, -(-n_sink // b))
 
 
@@ -258,18 +274,19 @@ def block_sparse_attention(Qp: np.ndarray, Kp: np.ndarray, Vp: np.ndarray, M: np
 # --------------------------------------------------------------------------
 def layer(Q: np.ndarray, K: np.ndarray, V: np.ndarray, *, T: int, H: int, W: int, block: int,
           sparsity: float, sink_frames: int = 0, sink_at_end: bool = True,
-          window=None, budget_mode: int = BUDGET_GLOBAL, q_blocks=None) -> dict:
-    """All stages for one (batch, head).  Q, K, V: [N, d] float64 in [T,H,W]
-    raster order.  Returns every intermediate."""
-    N = T * H * W
+          window=None, budget_mode: int = BUDGET_GLOBAL, q_blocks=None, text_tokens: int = 0) -> dict:
+    """All stages for one (batch, head).  Q, K, V: [N, d] float64, the video
+    tokens in [T,H,W] raster order followed by `text_tokens` text tokens.
+    Returns every intermediate."""
+    N = T * H * W + text_tokens
     assert Q.shape[0] == N
     wt, wh, ww = window if window is not None else default_window(block, T > 1)
-    perm = perm_table(T, H, W, wt, wh, ww, sink_frames, sink_at_end)
+    perm = perm_table(T, H, W, wt, wh, ww, sink_frames, sink_at_end, text_tokens)
     Qp, Kp, Vp = permute(Q, perm), permute(K, perm), permute(V, perm)
     qbar, kbar = pool_blocks(Qp, block), pool_blocks(Kp, block)
     S_hat = block_scores(qbar, kbar)
     Tb = n_blocks(N, block)
-    sb, se = sink_block_range(N, H * W, block, sink_frames, sink_at_end)
+    sb, se = sink_block_range(N, H * W, block, sink_frames, sink_at_end, text_tokens)
     k_row, k_sel = budget(Tb, se - sb, sparsity, budget_mode)
     M = select_blocks(S_hat, k_sel, sb, se)
     Op, lse = block_sparse_attention(Qp, Kp, Vp, M, block, q_blocks=q_blocks, return_lse=True)

@@ -138,3 +138,29 @@ def test_layer_sparse_equals_library_attention_in_raster_order():
     assert allow[:H * W].all() and allow[:, :H * W].all()
     achieved = 1.0 - r["M"].sum() / r["M"].size
     assert achieved >= 0.5
+
+
+def test_layer_with_text_tokens():
+    """Text tokens appended to the video tokens (Sec. 3.4, last paragraph): their rows and columns are
+    dense, like the first frame's; the whole layer equals library masked attention over all tokens;
+    with every block kept it is plain joint attention."""
+    rng = np.random.default_rng(16)
+    T, H, W, d, b, text = 4, 8, 8, 8, 32, 21
+    Nv, N = T * H * W, T * H * W + text
+    Q, K, V = (np.concatenate([_smooth(rng, T, H, W, d), rng.standard_normal((text, d))]) for _ in range(3))
+    r = orc.layer(Q, K, V, T=T, H=H, W=W, block=b, sparsity=0.5, sink_frames=1, window=(1, 4, 8), text_tokens=text)
+    sb, se = r["sink"]
+    assert (sb, se) == (6, 9) and r["M"].shape == (9, 9)      # body 192 tokens = 6 blocks; 64 + 21 dense tokens
+    assert r["M"][:, sb:se].all() and r["M"][sb:se].all() and (r["M"][:sb].sum(1) == r["k_row"]).all()
+    inv = orc.inverse_table(r["perm"])
+    blk_of = inv // b
+    allow = r["M"][blk_of][:, blk_of]
+    assert np.abs(r["O"] - sdpa_f64(Q, K, V, allow)).max() < 1e-12
+    assert allow[Nv:].all() and allow[:, Nv:].all()          # text queries see everything, everyone sees the text
+    assert allow[:H * W].all() and allow[:, :H * W].all()    # and the same for the first frame
+    dense = orc.layer(Q, K, V, T=T, H=H, W=W, block=b, sparsity=0.0, sink_frames=1, window=(2, 4, 4), text_tokens=text)
+    assert dense["M"].all() and np.abs(dense["O"] - sdpa_f64(Q, K, V)).max() < 1e-12
+    # text only (an image model with a prompt): the dense range is the text blocks
+    im = orc.layer(Q[H * W * 3:], K[H * W * 3:], V[H * W * 3:], T=1, H=H, W=W, block=b, sparsity=0.5,
+                   window=(1, 4, 8), text_tokens=text)
+    assert im["sink"] == (2, 3) and im["M"][:, 2].all() and im["M"][2].all()

@@ -18,12 +18,13 @@ def _rows(name):
 
 @pytest.mark.parametrize("row", list(_rows("perm_examples.txt")), ids=lambda r: r[0])
 def test_perm_matches_hand_written_examples(row):
-    _, thw, win, sink, perm = row
+    _, thw, win, sink, perm = row[:5]
+    text = int(row[5]) if len(row) > 5 else 0
     T, H, W = map(int, thw.split())
     wt, wh, ww = map(int, win.split())
     sf, at_end = map(int, sink.split())
     want = np.array(list(map(int, perm.split())))
-    got = orc.perm_table(T, H, W, wt, wh, ww, sf, bool(at_end))
+    got = orc.perm_table(T, H, W, wt, wh, ww, sf, bool(at_end), text)
     assert got.tolist() == want.tolist()
 
 
@@ -112,12 +113,13 @@ def test_round_trip_is_identity():
 
 @pytest.mark.parametrize("row", list(_rows("config_sizes.txt")), ids=lambda r: r[0])
 def test_sizes_of_the_workloads(row):
-    _, thw, b, sf, s, N, Tb, sb, nS, k_row, k_sel, kept = row
+    _, thw, b, sf, s, N, Tb, sb, nS, k_row, k_sel, kept = row[:12]
+    text = int(row[12]) if len(row) > 12 else 0
     T, H, W = map(int, thw.split())
     b, sf = int(b), int(sf)
-    assert T * H * W == int(N)
-    assert orc.n_blocks(T * H * W, b) == int(Tb)
-    begin, end = orc.sink_block_range(T * H * W, H * W, b, sf, True)
+    assert T * H * W + text == int(N)
+    assert orc.n_blocks(int(N), b) == int(Tb)
+    begin, end = orc.sink_block_range(int(N), H * W, b, sf, True, text)
     assert end - begin == int(nS)
     if int(nS):
         assert begin == int(sb) and end == int(Tb)
@@ -145,6 +147,27 @@ def test_sink_block_range_front_and_straddle():
     sb, se = orc.sink_block_range(1536, 256, 64, 1, True)
     first_frame_pos = np.flatnonzero(perm < 256)
     assert set(first_frame_pos // 64) == set(range(sb, se))
+
+
+def test_text_tokens_stay_in_order_at_the_end_and_are_dense():
+    T, H, W, text = 5, 7, 9, 11
+    video = orc.perm_table(T, H, W, 2, 4, 4, 1, True)
+    both = orc.perm_table(T, H, W, 2, 4, 4, 1, True, text)
+    assert both[:T * H * W].tolist() == video.tolist()            # the video part is untouched
+    assert both[T * H * W:].tolist() == list(range(T * H * W, T * H * W + text))
+    assert sorted(both.tolist()) == list(range(T * H * W + text))
+    # every block with a first-frame or text token is in the dense range, and no other block is
+    N, b = T * H * W + text, 16
+    sb, se = orc.sink_block_range(N, H * W, b, 1, True, text)
+    dense_pos = np.flatnonzero((both < H * W) | (both >= T * H * W))
+    assert set(dense_pos // b) == set(range(sb, se)) and se == orc.n_blocks(N, b)
+    # text without any sink frame: the dense range is the text blocks
+    assert orc.sink_block_range(4096 + 77, 4096, 128, 0, True, 77) == (32, 33)
+    assert orc.sink_block_range(4096 + 77, 4096, 128, 0, False, 77) == (32, 33)
+    with pytest.raises(ValueError):
+        orc.perm_table(T, H, W, 2, 4, 4, 1, False, text)          # two separate dense runs: not defined
+    with pytest.raises(ValueError):
+        orc.sink_block_range(N, H * W, b, 1, False, text)
 
 
 def test_bf16_decoding():
