@@ -11,6 +11,7 @@ Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -110,7 +111,7 @@ def cpu_baseline(wl, plan, q, k, v, dense_flops):
     head = 0
     Q, K, V = (orc.bf16_bits_to_f64(inputs.bf16_bits(x[0, head])) for x in (q, k, v))
     t0 = time.perf_counter()
-    perm = orc.perm_table(c.T, c.H, c.W, i.wt, i.wh, i.ww, c.sink_frames, bool(c.sink_at_end))
+    perm = orc.perm_table(c.T, c.H, c.W, i.wt, i.wh, i.ww, c.sink_frames, bool(c.sink_at_end), c.text_tokens)
     Qp, Kp, Vp = orc.permute(Q, perm), orc.permute(K, perm), orc.permute(V, perm)
     S_hat = orc.block_scores(orc.pool_blocks(Qp, c.block), orc.pool_blocks(Kp, c.block))
     M = orc.select_blocks(S_hat, i.k_sel, i.sink_block_begin, i.sink_block_end)
@@ -141,6 +142,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="video720p", choices=list(inputs.WORKLOADS))
     ap.add_argument("--sparsity", type=float, default=None)
+    ap.add_argument("--text-tokens", type=int, default=0,
+                    help="append this many text tokens (always-dense rows and columns) to the video tokens")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention baselines")
     ap.add_argument("--unfused", action="store_true",
@@ -156,9 +159,11 @@ def main():
     ensure_library()
     torch.cuda.set_device(0)
     wl = inputs.WORKLOADS[args.workload]
+    if args.text_tokens:
+        wl = dataclasses.replace(wl, text_tokens=args.text_tokens)
     s = wl.sparsity if args.sparsity is None else args.sparsity
     plan = rf2.Plan(batch=wl.batch, heads=wl.heads, head_dim=wl.head_dim, T=wl.T, H=wl.H, W=wl.W, block=wl.block,
-                    sparsity=s, sink_frames=wl.sink_frames)
+                    sparsity=s, sink_frames=wl.sink_frames, text_tokens=wl.text_tokens)
     i = plan.info
     q, k, v = inputs.make_qkv(wl, device="cuda")
     buf = plan.alloc("cuda")
@@ -182,7 +187,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: B{wl.batch} x {wl.heads} heads x d{wl.head_dim}, grid {wl.T}x{wl.H}x{wl.W}"
-                               f" = {wl.N} tokens, block {wl.block}, sparsity {s}, sink_frames {wl.sink_frames}",
+                               f" = {wl.T * wl.H * wl.W} tokens"
+                               + (f" + {wl.text_tokens} text tokens" if wl.text_tokens else "")
+                               + f", block {wl.block}, sparsity {s}, sink_frames {wl.sink_frames}",
                    "n_blocks": i.n_blocks, "k_row": i.k_row, "kept_pairs_per_head": i.kept_pairs_per_head,
                    "achieved_sparsity": round(i.achieved_sparsity, 4),
                    "inverse_permutation": "rf2_unpermute" if args.unfused else "fused into the attention epilogue"},
@@ -193,7 +200,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "block_sparse_attn_kernel",
                      "achieved": kept_flops / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": kept_flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                     "traffic": ATTN_TRAFFIC_BYTES.get(wl.name) if args.sparsity is None else None},
+                     "traffic": ATTN_TRAFFIC_BYTES.get(wl.name) if args.sparsity is None and not wl.text_tokens else None},
     }
     if not args.no_dense:
         cnt_dense = torch.full_like(buf["blk_cnt"], i.n_blocks)

@@ -73,13 +73,18 @@ typedef struct {
   int32_t qkv_layout;             /* RF2_LAYOUT_*: order of q, k, v (rf2_permute) and o (rf2_unpermute,
                                      rf2_block_sparse_attn_unpermuted); the gathers absorb it for free.
                                      Permuted tensors, means, lists and lse are always head-major. */
+  int32_t text_tokens;            /* tokens of the other modality appended after the T*H*W video tokens
+                                     (Sec. 3.4, last paragraph); they keep their order, sit at the very end of
+                                     the permuted sequence and are always dense, like the sink frames.
+                                     >= 0; with text_tokens > 0 the sink frames must be at the end. */
 } rf2_config;
 
 typedef struct {
-  int64_t N, N_pad;
+  int64_t N, N_pad;         /* N = T*H*W + text_tokens; N_pad = n_blocks * block */
   int32_t n_blocks;         /* Tb */
   int32_t last_block_valid; /* tokens in the last block, 1..b */
-  int32_t sink_block_begin, sink_block_end; /* [begin, end) of blocks holding >= 1 sink token; equal if none */
+  int32_t sink_block_begin, sink_block_end; /* [begin, end) of blocks holding >= 1 sink-frame or text token;
+                                               equal if none */
   int32_t k_row;            /* blocks kept by every non-sink row, sink blocks included */
   int32_t k_sel;            /* of those, chosen by score among non-sink columns = k_row - (end - begin) */
   int32_t wt, wh, ww;       /* window actually used */
@@ -92,12 +97,13 @@ typedef struct rf2_plan rf2_plan; /* opaque */
 
 /*
  * Host-only set-up (Sec. 3.3, 3.4): validates `cfg`, builds the permutation table
- *   perm[p] = raster index (t*H + h)*W + w of the token at permuted position p
+ *   perm[p] = input index of the token at permuted position p (video token (t, h, w) has
+ *             input index (t*H + h)*W + w; text token i has T*H*W + i)
  * and uploads it to the current device.  Window order: body frames (t >= sink_frames)
  * are cut into windows of (wt, wh, ww) tokens, edge windows truncated; windows are
  * listed in raster order of the window grid, tokens in raster order inside a window;
  * sink frames use (1, wh, ww) windows frame by frame and follow (sink_at_end) or
- * precede the body.  *out receives a plan to be released with rf2_plan_destroy.
+ * precede the body; text tokens come last, in their own order.  *out receives a plan to be released with rf2_plan_destroy.
  * If the process sees no HIP device the plan is host-only: rf2_plan_info and
  * rf2_plan_perm work, every compute call returns RF2_ERR_HIP.
  * Limits: N <= 2^24, Tb <= 2048, B*Hh <= 65535 (RF2_ERR_UNSUPPORTED beyond).

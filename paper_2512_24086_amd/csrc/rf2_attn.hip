@@ -157,7 +157,10 @@ __global__ void __launch_bounds__(BLK * 2, BLK >= 128 ? 2 : 1) block_sparse_attn
       entry = sink_per_xcd + u % plain_per_xcd;
     }
   }
-  const int qi = row_order[xcd * (sink_per_xcd + plain_per_xcd) + entry];
+  // The work table deals a head's rows to 8 shares of slightly different size (e.g. 29 sink rows:
+  // five shares of 4, three of 3); the share an XCD takes rotates with the head so that no XCD
+  // collects the large shares of every head.
+  const int qi = row_order[((xcd + bh) & 7) * (sink_per_xcd + plain_per_xcd) + entry];
   if (qi < 0) return;
   const size_t row_id = (size_t)bh * Tb + qi;
   int cnt = blk_cnt[row_id];

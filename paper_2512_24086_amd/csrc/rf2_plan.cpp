@@ -72,12 +72,16 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
   if (!(c.sparsity >= 0.0f && c.sparsity < 1.0f)) return RF2_ERR_INVALID_ARG;  // also rejects NaN
   if (c.budget_mode < RF2_BUDGET_GLOBAL || c.budget_mode > RF2_BUDGET_ROW_PLUS_SINK) return RF2_ERR_INVALID_ARG;
   if (c.qkv_layout != RF2_LAYOUT_BHND && c.qkv_layout != RF2_LAYOUT_BNHD) return RF2_ERR_INVALID_ARG;
+  if (c.text_tokens < 0) return RF2_ERR_INVALID_ARG;
+  // the always-dense tokens must form one run of the permuted sequence
+  if (c.text_tokens > 0 && c.sink_frames > 0 && !c.sink_at_end) return RF2_ERR_UNSUPPORTED;
   if (c.wt < 0 || c.wh < 0 || c.ww < 0) return RF2_ERR_INVALID_ARG;
   const bool win_default = (c.wt == 0 && c.wh == 0 && c.ww == 0);
   if (!win_default && (c.wt < 1 || c.wh < 1 || c.ww < 1)) return RF2_ERR_INVALID_ARG;
   if (c.head_dim != 64 && c.head_dim != 128) return RF2_ERR_UNSUPPORTED;
   if (c.block != 64 && c.block != 128) return RF2_ERR_UNSUPPORTED;
-  const int64_t N = (int64_t)c.T * c.H * c.W;
+  const int64_t n_video = (int64_t)c.T * c.H * c.W;
+  const int64_t N = n_video + c.text_tokens;
   if (N > (int64_t)1 << 24) return RF2_ERR_UNSUPPORTED;  // 16 Mi tokens: keeps every index in int32
   if ((int64_t)c.batch * c.heads > 65535) return RF2_ERR_UNSUPPORTED;  // grid y dimension
 
@@ -97,13 +101,13 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
   const int Tb = in.n_blocks;
   if (Tb > 2048) { delete p; return RF2_ERR_UNSUPPORTED; }  // one row of block scores must fit the selection kernel's LDS
 
-  // Sink blocks: every block that holds at least one sink-frame token (Sec. 3.4).
+  // Always-dense blocks: every block that holds at least one sink-frame or text token (Sec. 3.4).
   const int64_t frame = (int64_t)c.H * c.W;
   const int64_t n_sink = (int64_t)c.sink_frames * frame;
-  if (n_sink == 0) {
+  if (n_sink + c.text_tokens == 0) {
     in.sink_block_begin = in.sink_block_end = 0;
-  } else if (c.sink_at_end) {
-    in.sink_block_begin = (int32_t)((N - n_sink) / b);
+  } else if (c.sink_at_end || n_sink == 0) {
+    in.sink_block_begin = (int32_t)((N - n_sink - c.text_tokens) / b);
     in.sink_block_end = Tb;
   } else {
     in.sink_block_begin = 0;
@@ -153,6 +157,7 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
         p->inv[(size_t)n] = (int32_t)pos;
         p->perm[(size_t)pos] = (int32_t)n;
       }
+  for (int64_t n = n_video; n < N; ++n) p->inv[(size_t)n] = p->perm[(size_t)n] = (int32_t)n;   // text: in place, last
 
   // Work tables of the attention kernel.  Workgroup g runs on XCD g % 8.  A head's all-column
   // sink rows are dealt round-robin to the XCDs; each XCD also gets a contiguous range of the

@@ -39,10 +39,11 @@ class Workload:
     sink_frames: int
     sigma: float
     sweep: tuple = field(default=())   # extra sparsity points
+    text_tokens: int = 0               # tokens of the other modality appended after the video tokens
 
     @property
     def N(self) -> int:
-        return self.T * self.H * self.W
+        return self.T * self.H * self.W + self.text_tokens
 
     @property
     def n_blocks(self) -> int:
@@ -89,7 +90,7 @@ def _field(gen_cpu: torch.Generator, T: int, H: int, W: int, d: int, sigma: floa
 
 def make_tensor(wl: Workload, tensor_index: int, device="cpu", heads=None) -> torch.Tensor:
     """Tensor `tensor_index` (0=Q, 1=K, 2=V) of workload `wl`: [B, heads, N, d] bf16,
-    tokens in [T, H, W] raster order.  `heads` limits generation to a list of
+    video tokens in [T, H, W] raster order, then the text tokens if any.  `heads` limits generation to a list of
     head numbers (each head's values do not depend on which others are made)."""
     device = torch.device(device)
     head_list = list(range(wl.heads)) if heads is None else list(heads)
@@ -101,6 +102,9 @@ def make_tensor(wl: Workload, tensor_index: int, device="cpu", heads=None) -> to
             gen.manual_seed(seed * 100003 + (b * wl.heads + hd))
             x = _field(gen, wl.T, wl.H, wl.W, wl.head_dim, wl.sigma, device,
                        noise_seed=seed * 7919 + (b * wl.heads + hd))
+            if wl.text_tokens:
+                # text tokens have no spatial structure: i.i.d. unit-variance rows (drawn after the field)
+                x = torch.cat([x, torch.randn(wl.text_tokens, wl.head_dim, generator=gen).to(device)])
             out[b, k] = x.to(torch.bfloat16)
     return out
 

@@ -22,7 +22,7 @@ RF2_LAYOUT_BHND, RF2_LAYOUT_BNHD = 0, 1
 class rf2_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "heads", "head_dim", "T", "H", "W", "wt", "wh", "ww",
                                          "block", "sink_frames", "sink_at_end")] + \
-               [("sparsity", C.c_float), ("budget_mode", C.c_int32), ("qkv_layout", C.c_int32)]
+               [("sparsity", C.c_float), ("budget_mode", C.c_int32), ("qkv_layout", C.c_int32), ("text_tokens", C.c_int32)]
 
 
 class rf2_info(C.Structure):
@@ -93,9 +93,9 @@ class Plan:
     """Owner of an rf2_plan*; methods carry the names of the C entry points."""
 
     def __init__(self, *, batch, heads, head_dim, T, H, W, block, sparsity, sink_frames=0, sink_at_end=1,
-                 window=(0, 0, 0), budget_mode=RF2_BUDGET_GLOBAL, qkv_layout=RF2_LAYOUT_BHND):
+                 window=(0, 0, 0), budget_mode=RF2_BUDGET_GLOBAL, qkv_layout=RF2_LAYOUT_BHND, text_tokens=0):
         self.cfg = rf2_config(batch, heads, head_dim, T, H, W, window[0], window[1], window[2], block,
-                              sink_frames, int(sink_at_end), float(sparsity), budget_mode, qkv_layout)
+                              sink_frames, int(sink_at_end), float(sparsity), budget_mode, qkv_layout, text_tokens)
         self._h = C.c_void_p(0)
         _check(lib().rf2_plan_create(C.byref(self.cfg), C.byref(self._h)), "rf2_plan_create")
         self.info = rf2_info()

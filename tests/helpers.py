@@ -79,7 +79,8 @@ def gpu_lists_to_mask(blk_idx, blk_cnt, Tb):
 
 def make_plan(wl: inputs.Workload, sparsity=None, **kw):
     args = dict(batch=wl.batch, heads=wl.heads, head_dim=wl.head_dim, T=wl.T, H=wl.H, W=wl.W, block=wl.block,
-                sparsity=wl.sparsity if sparsity is None else sparsity, sink_frames=wl.sink_frames)
+                sparsity=wl.sparsity if sparsity is None else sparsity, sink_frames=wl.sink_frames,
+                text_tokens=wl.text_tokens)
     args.update(kw)
     return rf2.Plan(**args)
 
@@ -89,4 +90,4 @@ def oracle_layer(wl, q, k, v, head, plan, q_blocks=None, sparsity=None):
     Q, K, V = (f64(x[0, head]) for x in (q, k, v))
     return orc.layer(Q, K, V, T=c.T, H=c.H, W=c.W, block=c.block, sparsity=c.sparsity, sink_frames=c.sink_frames,
                      sink_at_end=bool(c.sink_at_end), window=(plan.info.wt, plan.info.wh, plan.info.ww),
-                     budget_mode=c.budget_mode, q_blocks=q_blocks)
+                     budget_mode=c.budget_mode, q_blocks=q_blocks, text_tokens=c.text_tokens)

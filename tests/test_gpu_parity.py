@@ -21,6 +21,9 @@ SMALL = {
     "image_small": (inputs.Workload("img", 9, 1, 2, 128, 1, 40, 36, 128, 0.5, 0, 0.3), {}),
     "one_block": (inputs.Workload("one", 10, 1, 1, 128, 1, 5, 7, 128, 0.5, 0, 0.3), {}),
     "row_incl_sink": (inputs.WORKLOADS["tiny"], dict(budget_mode=1, sparsity=0.6)),
+    # text tokens appended to the video tokens (ragged last block, always-dense tail)
+    "tiny_text": (inputs.Workload("tinytext", 13, 1, 2, 64, 6, 16, 16, 64, 0.5, 1, 0.3, text_tokens=40), {}),
+    "image_text_d128": (inputs.Workload("imgtext", 14, 1, 2, 128, 1, 40, 36, 128, 0.5, 0, 0.3, text_tokens=77), {}),
 }
 
 

@@ -39,7 +39,7 @@ def make_plan(**kw):
 @pytest.mark.parametrize("bad", [
     dict(batch=0), dict(heads=0), dict(T=0), dict(sink_frames=6), dict(sink_frames=-1), dict(sparsity=1.0),
     dict(sparsity=-0.1), dict(sparsity=float("nan")), dict(budget_mode=3), dict(window=(0, 4, 4)),
-    dict(window=(-1, 4, 4)), dict(sink_at_end=2), dict(qkv_layout=2), dict(qkv_layout=-1),
+    dict(window=(-1, 4, 4)), dict(sink_at_end=2), dict(qkv_layout=2), dict(qkv_layout=-1), dict(text_tokens=-1),
 ])
 def test_invalid_configs_are_rejected(bad):
     with pytest.raises(rf2.Rf2Error) as e:
@@ -47,7 +47,8 @@ def test_invalid_configs_are_rejected(bad):
     assert e.value.code == rf2.RF2_ERR_INVALID_ARG
 
 
-@pytest.mark.parametrize("bad", [dict(head_dim=96), dict(block=32), dict(T=4096, H=256, W=256)])
+@pytest.mark.parametrize("bad", [dict(head_dim=96), dict(block=32), dict(T=4096, H=256, W=256),
+                                 dict(text_tokens=5, sink_at_end=0)])   # dense tokens in two separate runs
 def test_unsupported_configs_are_rejected(bad):
     with pytest.raises(rf2.Rf2Error) as e:
         make_plan(**bad)
@@ -105,4 +106,24 @@ def test_ragged_tables_and_budget_modes(case, mode):
     sb, se = orc.sink_block_range(T * H * W, H * W, 64, sf, bool(at_end))
     assert (i.sink_block_begin, i.sink_block_end) == (sb, se)
     assert (i.k_row, i.k_sel) == orc.budget(i.n_blocks, se - sb, 0.6, mode)
+    p.close()
+
+
+@pytest.mark.parametrize("case", [
+    # T, H, W, block, window, sink_frames, text_tokens
+    (6, 16, 16, 64, (4, 4, 4), 1, 40), (5, 7, 9, 64, (2, 4, 4), 1, 11), (1, 64, 64, 128, (1, 8, 16), 0, 77),
+    (21, 45, 80, 128, (2, 8, 8), 1, 512), (3, 5, 6, 128, (2, 8, 8), 0, 300),
+])
+def test_text_tokens_tables_match_the_oracle(case):
+    T, H, W, b, win, sf, text = case
+    p = make_plan(T=T, H=H, W=W, block=b, window=win, sink_frames=sf, text_tokens=text, sparsity=0.7, head_dim=128)
+    i = p.info
+    N = T * H * W + text
+    assert (i.N, i.n_blocks) == (N, orc.n_blocks(N, b))
+    sb, se = orc.sink_block_range(N, H * W, b, sf, True, text)
+    assert (i.sink_block_begin, i.sink_block_end) == (sb, se)
+    assert (i.k_row, i.k_sel) == orc.budget(i.n_blocks, se - sb, 0.7)
+    perm, inv = p.rf2_plan_perm()
+    want = orc.perm_table(T, H, W, *win, sf, True, text)
+    assert np.array_equal(perm, want) and np.array_equal(inv, orc.inverse_table(want))
     p.close()
