@@ -69,9 +69,10 @@ def time_layer(plan, q, k, v, buf, steps, warmup, fused=True):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     names = ["permute_pool", "predict_mask", "block_sparse_attn", "unpermute"]
-    stages = {n: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(steps)) / steps
-              for i, n in enumerate(names)}
-    return wall_ms, stages
+    per_step = {n: sorted(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(steps)) for i, n in enumerate(names)}
+    stages = {n: sum(t) / steps for n, t in per_step.items()}
+    spread = {n: {"median": t[steps // 2], "min": t[0]} for n, t in per_step.items()}
+    return wall_ms, stages, spread
 
 
 def time_attn_only(plan, buf, idx, cnt, iters, warmup=1):
@@ -138,8 +139,8 @@ def cpu_baseline(wl, plan, q, k, v, dense_flops):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="video720p", choices=list(inputs.WORKLOADS))
     ap.add_argument("--sparsity", type=float, default=None)
     ap.add_argument("--text-tokens", type=int, default=0,
@@ -169,7 +170,8 @@ def main():
     buf = plan.alloc("cuda")
     torch.cuda.synchronize()
 
-    wall_ms, stages = time_layer(plan, q, k, v, buf, args.steps, args.warmup, fused=not args.unfused)
+    wall_ms, stages, spread = time_layer(plan, q, k, v, buf, args.steps, args.warmup, fused=not args.unfused)
+    mfma_peak, copy_peak = rf2.rf2_measure_peaks()        # ceilings measured on this machine, for context
     bh = wl.batch * wl.heads
     dense_flops = 4.0 * wl.N * wl.N * wl.head_dim * bh
     kept_flops = 4.0 * wl.block * wl.block * wl.head_dim * i.kept_pairs_per_head * bh
@@ -194,7 +196,12 @@ def main():
                    "achieved_sparsity": round(i.achieved_sparsity, 4),
                    "inverse_permutation": "rf2_unpermute" if args.unfused else "fused into the attention epilogue"},
         "stages_ms": {n: round(t, 4) for n, t in stages.items()},
+        "stages_ms_median_min": {n: [round(v["median"], 4), round(v["min"], 4)] for n, v in spread.items()
+                                 if n != "unpermute" or args.unfused},
         "stages_gbps": {n: round(g, 1) for n, g in gbps.items()},
+        "measured_peaks": {"mfma_bf16_loop_tflops": round(mfma_peak, 1), "copy_kernel_gbps": round(copy_peak, 1),
+                           "attn_frac_of_mfma_loop": round(kept_flops / (attn_ms * 1e-3) / 1e12 / mfma_peak, 4),
+                           "permute_pool_frac_of_copy": round(gbps["permute_pool"] / copy_peak, 4)},
         "attn": {"ms": round(attn_ms, 4), "kept_tflops": round(kept_flops / (attn_ms * 1e-3) / 1e12, 1),
                  "dense_equiv_tflops": round(dense_flops / (attn_ms * 1e-3) / 1e12, 1)},
         "roofline": {"bound": "mfma", "kernel": "block_sparse_attn_kernel",

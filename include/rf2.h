@@ -193,6 +193,17 @@ int rf2_block_sparse_attn_unpermuted(const rf2_plan* plan, const void* qp, const
 /* o[perm[p]] = op[p] for p < N.  op: [B, Hh, N_pad, d] bf16; o: [B, Hh, N, d] (or [B, N, Hh, d]) bf16. */
 int rf2_unpermute(const rf2_plan* plan, const void* op, void* o, void* stream);
 
+/*
+ * Measurement aid, not part of the layer: the ceilings of the device the calling thread is on, so
+ * that a benchmark can quote roofline fractions against measured as well as published peaks.
+ *   mfma_bf16_tflops : rate of a loop of nothing but v_mfma_f32_32x32x16_bf16 (4 independent chains
+ *                      per wavefront, 8 wavefronts per compute unit), TFLOP/s; may be NULL  (host, out)
+ *   copy_gbps        : read + write bandwidth of a plain copy kernel over 1 GiB, GB/s; may be NULL
+ *                                                                                         (host, out)
+ * Allocates (and frees) 2 GiB of device memory and synchronises with `stream`; takes ~0.1 s.
+ */
+int rf2_measure_peaks(double* mfma_bf16_tflops, double* copy_gbps, void* stream);
+
 /* Static description of an error code; for RF2_ERR_HIP the text of the last HIP error seen
  * by the calling thread is appended. */
 const char* rf2_strerror(int code);

@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "librf2.so")
-SOURCES = ["rf2_plan.cpp", "rf2_permute.hip", "rf2_mask.hip", "rf2_attn.hip"]
+SOURCES = ["rf2_plan.cpp", "rf2_permute.hip", "rf2_mask.hip", "rf2_attn.hip", "rf2_probe.hip"]
 # Packed-fp32 VALU forms are switched off on purpose (they have misbehaved on the target machines).
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -44,6 +44,7 @@ SIGNATURES = {
     "rf2_block_sparse_attn": (C.c_int, [C.c_void_p] * 9),
     "rf2_block_sparse_attn_unpermuted": (C.c_int, [C.c_void_p] * 9),
     "rf2_unpermute": (C.c_int, [C.c_void_p] * 4),
+    "rf2_measure_peaks": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
     "rf2_strerror": (C.c_char_p, [C.c_int]),
     "rf2_version": (C.c_int, []),
 }
@@ -87,6 +88,13 @@ def _stream(stream) -> C.c_void_p:
     if stream is None:
         stream = torch.cuda.current_stream()
     return C.c_void_p(stream.cuda_stream)
+
+
+def rf2_measure_peaks(stream=None):
+    """(bf16 MFMA-loop TFLOP/s, copy-kernel GB/s) measured on the current device."""
+    mfma, copy = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().rf2_measure_peaks(C.byref(mfma), C.byref(copy), _stream(stream)), "rf2_measure_peaks")
+    return mfma.value, copy.value
 
 
 class Plan:

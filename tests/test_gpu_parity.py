@@ -283,3 +283,11 @@ def test_token_major_layout_gives_identical_results(name):
     assert torch.equal(o_fused.view(torch.int16), buf_b["o"].view(torch.int16))
     plan_a.close()
     plan_b.close()
+
+
+def test_measured_peaks_are_plausible():
+    """The measurement aid returns the MFMA-loop rate and the copy bandwidth of this GPU."""
+    from paper_2512_24086_amd import rf2
+    mfma, copy = rf2.rf2_measure_peaks()
+    assert 500.0 < mfma <= 2600.0, mfma        # dense bf16 peak of the chip is 2.5 PFLOP/s
+    assert 1000.0 < copy <= 8200.0, copy       # HBM3E peak is 8 TB/s

@@ -63,6 +63,7 @@ def test_null_arguments_are_rejected():
     assert lib.rf2_predict_mask(*([None] * 9)) == rf2.RF2_ERR_INVALID_ARG
     assert lib.rf2_block_sparse_attn(*([None] * 9)) == rf2.RF2_ERR_INVALID_ARG
     assert lib.rf2_unpermute(*([None] * 4)) == rf2.RF2_ERR_INVALID_ARG
+    assert lib.rf2_measure_peaks(None, None, None) == rf2.RF2_ERR_INVALID_ARG
     assert lib.rf2_plan_destroy(None) == rf2.RF2_OK
 
 
