@@ -218,6 +218,41 @@ def selection_gap(S_hat: np.ndarray, k_sel: int, sink_begin: int, sink_end: int)
     return gap
 
 
+def select_blocks_cdf(S_hat: np.ndarray, tau: float, d: int, sink_begin: int, sink_end: int):
+    """Threshold variant of the selection (the cumulative-mass rule Sec. 2 describes for
+    online adaptive patterns, applied to the block scores of eq. 7): for every non-sink
+    row, softmax over the non-sink columns of S_hat / sqrt(d); the columns are taken in
+    the order of eq. (8) (largest score first, equal scores: lower column first) until
+    their cumulative probability reaches tau; at least one is taken.  Sink columns are
+    always kept, sink rows keep every column (Sec. 3.4).  Returns (M, margin): margin[i]
+    = distance between tau and the nearer of the cumulative probabilities just before and
+    just after the last column taken (+inf for sink rows and rows that take everything) --
+    a row whose margin is tiny may legitimately be cut one column earlier or later by
+    arithmetic of lower precision."""
+    if not (0.0 < tau < 1.0):
+        raise ValueError("tau must lie strictly between 0 and 1")
+    Tb = S_hat.shape[0]
+    M = np.zeros((Tb, Tb), dtype=bool)
+    margin = np.full(Tb, np.inf)
+    cand = np.array([j for j in range(Tb) if not (sink_begin <= j < sink_end)], dtype=np.int64)
+    for i in range(Tb):
+        if sink_begin <= i < sink_end or cand.size == 0:
+            M[i, :] = True
+            continue
+        z = S_hat[i, cand] / math.sqrt(d)
+        p = np.exp(z - z.max())
+        p /= p.sum()
+        order = np.lexsort((cand, -z))
+        cum = np.cumsum(p[order])
+        n = int(np.argmax(cum >= tau)) + 1 if (cum >= tau).any() else cand.size
+        M[i, cand[order[:n]]] = True
+        M[i, sink_begin:sink_end] = True
+        if n < cand.size:
+            before = cum[n - 2] if n >= 2 else 0.0
+            margin[i] = min(abs(cum[n - 1] - tau), abs(tau - before))
+    return M, margin
+
+
 def mask_to_lists(M: np.ndarray) -> list[np.ndarray]:
     """Ascending kept-column list of every row."""
     return [np.flatnonzero(M[i]).astype(np.int32) for i in range(M.shape[0])]
@@ -274,7 +309,8 @@ def block_sparse_attention(Qp: np.ndarray, Kp: np.ndarray, Vp: np.ndarray, M: np
 # --------------------------------------------------------------------------
 def layer(Q: np.ndarray, K: np.ndarray, V: np.ndarray, *, T: int, H: int, W: int, block: int,
           sparsity: float, sink_frames: int = 0, sink_at_end: bool = True,
-          window=None, budget_mode: int = BUDGET_GLOBAL, q_blocks=None, text_tokens: int = 0) -> dict:
+          window=None, budget_mode: int = BUDGET_GLOBAL, q_blocks=None, text_tokens: int = 0,
+          cdf_threshold: float | None = None) -> dict:
     """All stages for one (batch, head).  Q, K, V: [N, d] float64, the video
     tokens in [T,H,W] raster order followed by `text_tokens` text tokens.
     Returns every intermediate."""
@@ -288,9 +324,14 @@ def layer(Q: np.ndarray, K: np.ndarray, V: np.ndarray, *, T: int, H: int, W: int
     Tb = n_blocks(N, block)
     sb, se = sink_block_range(N, H * W, block, sink_frames, sink_at_end, text_tokens)
     k_row, k_sel = budget(Tb, se - sb, sparsity, budget_mode)
-    M = select_blocks(S_hat, k_sel, sb, se)
+    if cdf_threshold is None:
+        M = select_blocks(S_hat, k_sel, sb, se)
+        gap = selection_gap(S_hat, k_sel, sb, se)
+    else:                       # cumulative-mass selection: row lengths vary, the budget does not apply
+        M, gap = select_blocks_cdf(S_hat, cdf_threshold, Q.shape[1], sb, se)
+        k_row, k_sel = Tb, 0
     Op, lse = block_sparse_attention(Qp, Kp, Vp, M, block, q_blocks=q_blocks, return_lse=True)
     O = unpermute(Op, perm)
     return dict(perm=perm, Qp=Qp, Kp=Kp, Vp=Vp, qbar=qbar, kbar=kbar, S_hat=S_hat, M=M,
                 sink=(sb, se), k_row=k_row, k_sel=k_sel, Op=Op, lse=lse, O=O,
-                gap=selection_gap(S_hat, k_sel, sb, se))
+                gap=gap)

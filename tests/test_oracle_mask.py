@@ -109,3 +109,75 @@ def test_selection_gap():
 def test_mask_to_lists():
     M = np.array([[1, 0, 1], [0, 0, 1], [1, 1, 1]], dtype=bool)
     assert [l.tolist() for l in orc.mask_to_lists(M)] == [[0, 2], [2], [0, 1, 2]]
+
+
+def _cdf_by_loops(S, tau, d, sb, se):
+    """Independent statement of the cumulative-mass rule with explicit loops."""
+    Tb = S.shape[0]
+    M = np.zeros((Tb, Tb), dtype=bool)
+    for i in range(Tb):
+        if sb <= i < se:
+            M[i] = True
+            continue
+        cols = [j for j in range(Tb) if not (sb <= j < se)]
+        w = {j: np.exp(S[i, j] / np.sqrt(d)) for j in cols}
+        total = sum(w.values())
+        taken, mass = [], 0.0
+        while cols and (not taken or mass < tau * total):
+            best = max(cols, key=lambda j: (S[i, j], -j))        # largest score, then lowest column
+            cols.remove(best)
+            taken.append(best)
+            mass += w[best]
+        M[i, taken] = True
+        M[i, sb:se] = True
+    return M
+
+
+@pytest.mark.parametrize("Tb,sb,se,tau", [(12, 9, 12, 0.5), (12, 0, 0, 0.9), (9, 0, 3, 0.3), (17, 14, 17, 0.97)])
+def test_cdf_selection_vs_loops(Tb, sb, se, tau):
+    rng = np.random.default_rng(Tb * 7 + int(tau * 100))
+    S = rng.standard_normal((Tb, Tb)) * 6.0
+    M, margin = orc.select_blocks_cdf(S, tau, 16, sb, se)
+    assert np.array_equal(M, _cdf_by_loops(S, tau, 16, sb, se))
+    assert M[:, sb:se].all() and M[sb:se].all()
+    assert (margin[sb:se] == np.inf).all() and (margin >= 0).all()
+
+
+def test_cdf_selection_closed_cases():
+    Tb, d = 10, 4
+    S = np.zeros((Tb, Tb))                                  # equal scores: each of the 8 candidates has mass 1/8
+    M, margin = orc.select_blocks_cdf(S, 0.5, d, 8, 10)
+    assert (M[:8, :8].sum(1) == 4).all() and M[0, :4].all()  # 4 * 1/8 reaches 0.5; lowest columns first
+    assert np.allclose(margin[:8], 0.0)                      # cut exactly on the threshold: flagged as a near-tie
+    M, _ = orc.select_blocks_cdf(S, 0.51, d, 8, 10)
+    assert (M[:8, :8].sum(1) == 5).all()
+    # one dominant column: it alone carries the mass for any tau below its probability
+    S = np.zeros((Tb, Tb)); S[:, 3] = 40.0
+    M, _ = orc.select_blocks_cdf(S, 0.99, d, 8, 10)
+    assert (M[:8, :8].sum(1) == 1).all() and M[:8, 3].all()
+    # a larger tau keeps a superset; tau close to 1 keeps (nearly) everything
+    rng = np.random.default_rng(3)
+    S = rng.standard_normal((Tb, Tb)) * 3.0
+    prev = None
+    for tau in (0.1, 0.4, 0.7, 0.95, 0.999999):
+        M, _ = orc.select_blocks_cdf(S, tau, d, 8, 10)
+        assert prev is None or (M | ~prev).all()
+        prev = M
+    assert prev[:8, :8].sum() >= 8 * 7
+    with pytest.raises(ValueError):
+        orc.select_blocks_cdf(S, 1.0, d, 8, 10)
+
+
+def test_layer_with_cdf_selection_equals_library_masked_attention():
+    import torch
+    rng = np.random.default_rng(21)
+    T, H, W, d, b = 3, 8, 8, 8, 16
+    # block means of distinct sizes, so that the rows' score distributions (and lengths) differ
+    X = [rng.standard_normal((T * H * W, d)) + (rng.uniform(0, 5, (T * H * W // b, 1, 1)) * rng.standard_normal((T * H * W // b, 1, d))).repeat(b, 1).reshape(-1, d)
+         for _ in range(3)]
+    r = orc.layer(*X, T=T, H=H, W=W, block=b, sparsity=0.5, sink_frames=1, window=(1, 2, 8), cdf_threshold=0.6)
+    assert r["k_row"] == r["M"].shape[0] and len(set(r["M"][:8].sum(1))) > 1      # row lengths vary
+    inv = orc.inverse_table(r["perm"])
+    allow = torch.from_numpy(r["M"][inv // b][:, inv // b])
+    want = torch.nn.functional.scaled_dot_product_attention(*(torch.from_numpy(x)[None] for x in X), attn_mask=allow[None])[0]
+    assert np.abs(r["O"] - want.numpy()).max() < 1e-12
