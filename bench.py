@@ -115,7 +115,10 @@ def cpu_baseline(wl, plan, q, k, v, dense_flops):
     perm = orc.perm_table(c.T, c.H, c.W, i.wt, i.wh, i.ww, c.sink_frames, bool(c.sink_at_end), c.text_tokens)
     Qp, Kp, Vp = orc.permute(Q, perm), orc.permute(K, perm), orc.permute(V, perm)
     S_hat = orc.block_scores(orc.pool_blocks(Qp, c.block), orc.pool_blocks(Kp, c.block))
-    M = orc.select_blocks(S_hat, i.k_sel, i.sink_block_begin, i.sink_block_end)
+    if c.select_mode == rf2.RF2_SELECT_CDF:
+        M, _ = orc.select_blocks_cdf(S_hat, float(c.cdf_threshold), c.head_dim, i.sink_block_begin, i.sink_block_end)
+    else:
+        M = orc.select_blocks(S_hat, i.k_sel, i.sink_block_begin, i.sink_block_end)
     t_pre = time.perf_counter() - t0
     Tb = i.n_blocks
     sample = list(range(Tb))                           # every Q block of this one head: ~10 s of oracle time
@@ -126,7 +129,7 @@ def cpu_baseline(wl, plan, q, k, v, dense_flops):
     t_unp0 = time.perf_counter()
     orc.unpermute(Op, perm)
     t_unp = time.perf_counter() - t_unp0
-    per_head = t_pre + t_unp + t_attn * (i.kept_pairs_per_head / pairs)
+    per_head = t_pre + t_unp + t_attn * (int(M.sum()) / pairs)
     layer_s = per_head * c.batch * c.heads
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {"value": dense_flops / layer_s / 1e12, "unit": "TFLOP/s dense-equivalent (extrapolated)",
@@ -145,6 +148,8 @@ def main():
     ap.add_argument("--sparsity", type=float, default=None)
     ap.add_argument("--text-tokens", type=int, default=0,
                     help="append this many text tokens (always-dense rows and columns) to the video tokens")
+    ap.add_argument("--cdf", type=float, default=None,
+                    help="cumulative-mass block selection with this threshold instead of top-n (row lengths vary)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention baselines")
     ap.add_argument("--unfused", action="store_true",
@@ -164,7 +169,7 @@ def main():
         wl = dataclasses.replace(wl, text_tokens=args.text_tokens)
     s = wl.sparsity if args.sparsity is None else args.sparsity
     plan = rf2.Plan(batch=wl.batch, heads=wl.heads, head_dim=wl.head_dim, T=wl.T, H=wl.H, W=wl.W, block=wl.block,
-                    sparsity=s, sink_frames=wl.sink_frames, text_tokens=wl.text_tokens)
+                    sparsity=s, sink_frames=wl.sink_frames, text_tokens=wl.text_tokens, cdf_threshold=args.cdf)
     i = plan.info
     q, k, v = inputs.make_qkv(wl, device="cuda")
     buf = plan.alloc("cuda")
@@ -174,7 +179,10 @@ def main():
     mfma_peak, copy_peak = rf2.rf2_measure_peaks()        # ceilings measured on this machine, for context
     bh = wl.batch * wl.heads
     dense_flops = 4.0 * wl.N * wl.N * wl.head_dim * bh
-    kept_flops = 4.0 * wl.block * wl.block * wl.head_dim * i.kept_pairs_per_head * bh
+    kept_pairs = i.kept_pairs_per_head * bh
+    if args.cdf is not None:            # data dependent: count what the mask kernel kept
+        kept_pairs = int(buf["blk_cnt"].sum().item())
+    kept_flops = 4.0 * wl.block * wl.block * wl.head_dim * kept_pairs
     attn_ms = stages["block_sparse_attn"]
     itemsize = 2
     tensor_bytes = bh * wl.N * wl.head_dim * itemsize
@@ -192,8 +200,9 @@ def main():
                                f" = {wl.T * wl.H * wl.W} tokens"
                                + (f" + {wl.text_tokens} text tokens" if wl.text_tokens else "")
                                + f", block {wl.block}, sparsity {s}, sink_frames {wl.sink_frames}",
-                   "n_blocks": i.n_blocks, "k_row": i.k_row, "kept_pairs_per_head": i.kept_pairs_per_head,
-                   "achieved_sparsity": round(i.achieved_sparsity, 4),
+                   "selection": "top-n (eq. 8)" if args.cdf is None else f"cumulative mass >= {args.cdf}",
+                   "n_blocks": i.n_blocks, "k_row": i.k_row, "kept_pairs_per_head": kept_pairs / bh,
+                   "achieved_sparsity": round(1.0 - kept_pairs / bh / i.n_blocks ** 2, 4),
                    "inverse_permutation": "rf2_unpermute" if args.unfused else "fused into the attention epilogue"},
         "stages_ms": {n: round(t, 4) for n, t in stages.items()},
         "stages_ms_median_min": {n: [round(v["median"], 4), round(v["min"], 4)] for n, v in spread.items()
@@ -207,7 +216,8 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "block_sparse_attn_kernel",
                      "achieved": kept_flops / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": kept_flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                     "traffic": ATTN_TRAFFIC_BYTES.get(wl.name) if args.sparsity is None and not wl.text_tokens else None},
+                     "traffic": (ATTN_TRAFFIC_BYTES.get(wl.name)
+                                 if args.sparsity is None and not wl.text_tokens and args.cdf is None else None)},
     }
     if not args.no_dense:
         cnt_dense = torch.full_like(buf["blk_cnt"], i.n_blocks)

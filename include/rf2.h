@@ -54,6 +54,17 @@ enum {
   RF2_BUDGET_ROW_PLUS_SINK = 2  /* each row selects ceil((1-s) Tb) blocks in addition to the sink */
 };
 
+/* How a row chooses its non-sink columns. */
+enum {
+  RF2_SELECT_TOPN = 0, /* eq. (8): the k_sel largest scores, k_sel from `sparsity` and `budget_mode` */
+  RF2_SELECT_CDF = 1   /* cumulative-mass rule (the paper's Sec. 2 describes it for online adaptive patterns):
+                          softmax over the non-sink columns of S_hat / sqrt(d); columns are taken in the
+                          order of eq. (8) until their cumulative probability reaches `cdf_threshold`; at
+                          least one.  Row lengths then depend on the data: rf2_info.k_row = Tb is only the
+                          capacity of a list row, k_sel = 0, kept_pairs_per_head = -1 and
+                          achieved_sparsity = -1 (unknown before the mask exists); `sparsity` is ignored. */
+};
+
 /* Memory order of the caller's q, k, v and o tensors (the paper only says Q, K, V are N x d per head). */
 enum {
   RF2_LAYOUT_BHND = 0, /* [B, Hh, N, d]: one contiguous N x d matrix per head */
@@ -77,6 +88,8 @@ typedef struct {
                                      (Sec. 3.4, last paragraph); they keep their order, sit at the very end of
                                      the permuted sequence and are always dense, like the sink frames.
                                      >= 0; with text_tokens > 0 the sink frames must be at the end. */
+  int32_t select_mode;            /* RF2_SELECT_* */
+  float cdf_threshold;            /* tau of RF2_SELECT_CDF, strictly between 0 and 1; ignored otherwise */
 } rf2_config;
 
 typedef struct {
@@ -145,11 +158,16 @@ int rf2_permute(const rf2_plan* plan, const void* q, const void* k, const void* 
 /*
  * Eq. (7): S_hat[i][j] = <qbar_i, kbar_j> in fp32; eq. (8): every non-sink row i keeps
  * the k_sel non-sink columns with the largest S_hat[i][.] (equal scores: lower column
- * first) and all sink columns; sink rows keep every column (Sec. 3.4).
+ * first) and all sink columns; sink rows keep every column (Sec. 3.4).  With
+ * RF2_SELECT_CDF the non-sink columns are chosen by cumulative softmax mass instead and the
+ * count of a row is whatever the rule yields (sums are fp32: a row whose cumulative mass
+ * passes the threshold by less than ~1e-5 may be cut one column earlier or later than in
+ * exact arithmetic).
  *   blk_idx : [B, Hh, Tb, k_row] int32, kept columns of each row in ascending order;
  *             for sink rows the first k_row entries of the row are 0..k_row-1 and the
  *             row is flagged dense by its count                            (out)
- *   blk_cnt : [B, Hh, Tb] int32: k_row, or Tb for a row that keeps everything (out)
+ *   blk_cnt : [B, Hh, Tb] int32: k_row (CDF: the row's own count), or Tb for a row that
+ *             keeps everything                                             (out)
  *   mask_dense : optional [B, Hh, Tb, Tb] uint8 0/1, may be NULL            (out)
  *   scores  : optional [B, Hh, Tb, Tb] fp32 S_hat, may be NULL              (out)
  *   workspace : rf2_info.workspace_bytes of device memory (may be NULL when 0)

@@ -3,6 +3,9 @@
 // kernel.  A workgroup owns 16 rows of one head: its 4 wavefronts first fill a 16 x Tb
 // score strip in LDS, then each wavefront selects 4 of the rows with a bitwise threshold
 // search over order-preserving integer keys and emits the ascending block list.
+// The cumulative-mass variant (RF2_SELECT_CDF) runs the same search on probability mass
+// instead of counts: the threshold is the largest key whose upper set carries >= tau of the
+// row's softmax mass.
 #include "rf2_internal.h"
 
 namespace {
@@ -18,11 +21,23 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 
 __device__ __forceinline__ int popc64(unsigned long long m) { return __builtin_popcountll(m); }
 
-template <int D, int EMAX>
+// Butterfly reductions: every lane ends with the same bits (a + b and b + a are the same float).
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+template <int D, int EMAX, bool CDF>
 __global__ void __launch_bounds__(256) predict_mask_kernel(
     const float* __restrict__ qbar, const float* __restrict__ kbar, int32_t* __restrict__ blk_idx,
     int32_t* __restrict__ blk_cnt, uint8_t* __restrict__ mask_dense, float* __restrict__ scores,
-    int Tb, int LD, int sink_begin, int sink_end, int k_row, int k_sel) {
+    int Tb, int LD, int sink_begin, int sink_end, int k_row, int k_sel, float tau, float scale_log2) {
   extern __shared__ __attribute__((aligned(16))) float sc[];   // [16][LD]
   const int bh = blockIdx.y;
   const int i0 = blockIdx.x * 16;
@@ -84,31 +99,67 @@ __global__ void __launch_bounds__(256) predict_mask_kernel(
       const bool cand = (e < E) && (j < Tb) && !(j >= sink_begin && j < sink_end);
       key[e] = cand ? order_key(sc[r * LD + j]) : 0u;   // 0 is below the key of every finite float
     }
-    // Largest T with |{key >= T}| >= k_sel, built bit by bit: T is the k_sel-th largest key.
     uint32_t T = 0xffffffffu;
-    if (k_sel > 0) {
+    int need_eq;                                      // equal keys to take, lowest column first
+    if constexpr (!CDF) {
+      // Largest T with |{key >= T}| >= k_sel, built bit by bit: T is the k_sel-th largest key.
+      if (k_sel > 0) {
+        T = 0u;
+        for (int bit = 31; bit >= 0; --bit) {
+          const uint32_t cand = T | (1u << bit);
+          int cnt = 0;
+#pragma unroll
+          for (int e = 0; e < EMAX; ++e)
+            if (e < E) cnt += popc64(__builtin_amdgcn_ballot_w64(key[e] >= cand));
+          if (cnt >= k_sel) T = cand;
+        }
+      }
+      int greater = 0;
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e)
+        if (e < E) greater += popc64(__builtin_amdgcn_ballot_w64(key[e] > T));
+      need_eq = k_sel - greater;
+    } else {
+      // Softmax mass of every candidate (relative to the row maximum, unnormalised), then the
+      // largest T whose upper set {key >= T} carries at least tau of the total: the columns above
+      // T are the shortest prefix of the descending order that reaches tau, up to ties at T.
+      float mx = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e)
+        if (key[e] != 0u) mx = fmaxf(mx, sc[r * LD + 64 * e + lane]);
+      mx = wave_max(mx);
+      float ev[EMAX], part = 0.f;
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e) {
+        ev[e] = (key[e] != 0u) ? __builtin_amdgcn_exp2f((sc[r * LD + 64 * e + lane] - mx) * scale_log2) : 0.f;
+        part += ev[e];
+      }
+      const float target = tau * wave_sum(part);
       T = 0u;
       for (int bit = 31; bit >= 0; --bit) {
         const uint32_t cand = T | (1u << bit);
-        int cnt = 0;
+        float mass = 0.f;
 #pragma unroll
-        for (int e = 0; e < EMAX; ++e)
-          if (e < E) cnt += popc64(__builtin_amdgcn_ballot_w64(key[e] >= cand));
-        if (cnt >= k_sel) T = cand;
+        for (int e = 0; e < EMAX; ++e) mass += (key[e] >= cand) ? ev[e] : 0.f;
+        if (wave_sum(mass) >= target) T = cand;
       }
-    }
-    int greater = 0;
+      float above = 0.f, tie = 0.f;
 #pragma unroll
-    for (int e = 0; e < EMAX; ++e)
-      if (e < E) greater += popc64(__builtin_amdgcn_ballot_w64(key[e] > T));
-    const int need_eq = k_sel - greater;              // equal keys to take, lowest column first
+      for (int e = 0; e < EMAX; ++e) {
+        above += (key[e] > T) ? ev[e] : 0.f;
+        tie = fmaxf(tie, (key[e] == T) ? ev[e] : 0.f);
+      }
+      above = wave_sum(above);
+      tie = wave_max(tie);                            // equal keys have equal mass
+      need_eq = max(1, (int)ceilf((target - above) / tie));
+    }
     int eq_run = 0, out_run = 0;
 #pragma unroll
     for (int e = 0; e < EMAX; ++e) {
       if (e < E) {
         const int j = 64 * e + lane;
         const bool is_sink = (j < Tb) && (j >= sink_begin) && (j < sink_end);
-        const bool eq = (key[e] == T) && (k_sel > 0);
+        const bool eq = (key[e] == T) && (CDF ? key[e] != 0u : k_sel > 0);
         const unsigned long long eq_m = __builtin_amdgcn_ballot_w64(eq);
         const bool sel = is_sink || (key[e] > T) || (eq && (eq_run + popc64(eq_m & lt_mask) < need_eq));
         const unsigned long long sel_m = __builtin_amdgcn_ballot_w64(sel);
@@ -118,7 +169,7 @@ __global__ void __launch_bounds__(256) predict_mask_kernel(
         out_run += popc64(sel_m);
       }
     }
-    if (lane == 0) blk_cnt[(size_t)bh * Tb + i] = out_run;   // == k_row by construction
+    if (lane == 0) blk_cnt[(size_t)bh * Tb + i] = out_run;   // top-n: == k_row by construction
   }
 }
 
@@ -138,13 +189,15 @@ extern "C" int rf2_predict_mask(const rf2_plan* plan, const float* qbar, const f
   const size_t lds = (size_t)16 * LD * sizeof(float);
   const dim3 grid((Tb + 15) / 16, c.batch * c.heads, 1);
   hipStream_t st = (hipStream_t)stream;
+  const bool cdf = (c.select_mode == RF2_SELECT_CDF);
+  const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)c.head_dim));
 #define RF2_MASK_CASE(DD, EE)                                                                                   \
   {                                                                                                             \
-    auto kern = predict_mask_kernel<DD, EE>;                                                                    \
+    auto kern = cdf ? predict_mask_kernel<DD, EE, true> : predict_mask_kernel<DD, EE, false>;                   \
     if (lds > 48 * 1024)                                                                                        \
       RF2_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));    \
     kern<<<grid, 256, lds, st>>>(qbar, kbar, blk_idx, blk_cnt, mask_dense, scores, Tb, LD, in.sink_block_begin, \
-                                 in.sink_block_end, in.k_row, in.k_sel);                                        \
+                                 in.sink_block_end, in.k_row, in.k_sel, c.cdf_threshold, scale_log2);            \
     RF2_LAUNCH_CHECK();                                                                                         \
     return RF2_OK;                                                                                              \
   }

@@ -73,6 +73,8 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
   if (c.budget_mode < RF2_BUDGET_GLOBAL || c.budget_mode > RF2_BUDGET_ROW_PLUS_SINK) return RF2_ERR_INVALID_ARG;
   if (c.qkv_layout != RF2_LAYOUT_BHND && c.qkv_layout != RF2_LAYOUT_BNHD) return RF2_ERR_INVALID_ARG;
   if (c.text_tokens < 0) return RF2_ERR_INVALID_ARG;
+  if (c.select_mode != RF2_SELECT_TOPN && c.select_mode != RF2_SELECT_CDF) return RF2_ERR_INVALID_ARG;
+  if (c.select_mode == RF2_SELECT_CDF && !(c.cdf_threshold > 0.0f && c.cdf_threshold < 1.0f)) return RF2_ERR_INVALID_ARG;
   // the always-dense tokens must form one run of the permuted sequence
   if (c.text_tokens > 0 && c.sink_frames > 0 && !c.sink_at_end) return RF2_ERR_UNSUPPORTED;
   if (c.wt < 0 || c.wh < 0 || c.ww < 0) return RF2_ERR_INVALID_ARG;
@@ -133,6 +135,12 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
   in.k_sel = nS >= Tb ? 0 : k_row - nS;
   in.kept_pairs_per_head = (int64_t)(Tb - nS) * k_row + (int64_t)nS * Tb;
   in.achieved_sparsity = 1.0 - (double)in.kept_pairs_per_head / ((double)Tb * Tb);
+  if (c.select_mode == RF2_SELECT_CDF) {   // row lengths depend on the data: k_row is the list capacity
+    in.k_row = Tb;
+    in.k_sel = 0;
+    in.kept_pairs_per_head = -1;
+    in.achieved_sparsity = -1.0;
+  }
   in.workspace_bytes = 0;
 
   // Permutation tables from the closed form.

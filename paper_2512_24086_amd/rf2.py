@@ -17,12 +17,14 @@ RF2_OK = 0
 RF2_ERR_INVALID_ARG, RF2_ERR_UNSUPPORTED, RF2_ERR_ALLOC, RF2_ERR_HIP = -1, -2, -3, -4
 RF2_BUDGET_GLOBAL, RF2_BUDGET_ROW_INCL_SINK, RF2_BUDGET_ROW_PLUS_SINK = 0, 1, 2
 RF2_LAYOUT_BHND, RF2_LAYOUT_BNHD = 0, 1
+RF2_SELECT_TOPN, RF2_SELECT_CDF = 0, 1
 
 
 class rf2_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "heads", "head_dim", "T", "H", "W", "wt", "wh", "ww",
                                          "block", "sink_frames", "sink_at_end")] + \
-               [("sparsity", C.c_float), ("budget_mode", C.c_int32), ("qkv_layout", C.c_int32), ("text_tokens", C.c_int32)]
+               [("sparsity", C.c_float), ("budget_mode", C.c_int32), ("qkv_layout", C.c_int32), ("text_tokens", C.c_int32),
+                ("select_mode", C.c_int32), ("cdf_threshold", C.c_float)]
 
 
 class rf2_info(C.Structure):
@@ -101,9 +103,12 @@ class Plan:
     """Owner of an rf2_plan*; methods carry the names of the C entry points."""
 
     def __init__(self, *, batch, heads, head_dim, T, H, W, block, sparsity, sink_frames=0, sink_at_end=1,
-                 window=(0, 0, 0), budget_mode=RF2_BUDGET_GLOBAL, qkv_layout=RF2_LAYOUT_BHND, text_tokens=0):
+                 window=(0, 0, 0), budget_mode=RF2_BUDGET_GLOBAL, qkv_layout=RF2_LAYOUT_BHND, text_tokens=0,
+                 cdf_threshold=None):
         self.cfg = rf2_config(batch, heads, head_dim, T, H, W, window[0], window[1], window[2], block,
-                              sink_frames, int(sink_at_end), float(sparsity), budget_mode, qkv_layout, text_tokens)
+                              sink_frames, int(sink_at_end), float(sparsity), budget_mode, qkv_layout, text_tokens,
+                              RF2_SELECT_TOPN if cdf_threshold is None else RF2_SELECT_CDF,
+                              0.0 if cdf_threshold is None else float(cdf_threshold))
         self._h = C.c_void_p(0)
         _check(lib().rf2_plan_create(C.byref(self.cfg), C.byref(self._h)), "rf2_plan_create")
         self.info = rf2_info()

@@ -10,6 +10,7 @@ from paper_2512_24086_amd import inputs, rf2
 ATTN_MAX_ABS = 2e-2
 ATTN_MEAN_ABS = 2e-3
 TIE_GAP = 1e-3          # rows whose selection-boundary score gap is below this may differ
+CDF_TIE = 2e-5          # cumulative-mass selection: rows cut within this (normalised mass) of tau may differ (fp32 sums of <= 2048 terms)
 
 
 def f64(t: torch.Tensor) -> np.ndarray:
@@ -90,4 +91,5 @@ def oracle_layer(wl, q, k, v, head, plan, q_blocks=None, sparsity=None):
     Q, K, V = (f64(x[0, head]) for x in (q, k, v))
     return orc.layer(Q, K, V, T=c.T, H=c.H, W=c.W, block=c.block, sparsity=c.sparsity, sink_frames=c.sink_frames,
                      sink_at_end=bool(c.sink_at_end), window=(plan.info.wt, plan.info.wh, plan.info.ww),
-                     budget_mode=c.budget_mode, q_blocks=q_blocks, text_tokens=c.text_tokens)
+                     budget_mode=c.budget_mode, q_blocks=q_blocks, text_tokens=c.text_tokens,
+                     cdf_threshold=float(c.cdf_threshold) if c.select_mode == rf2.RF2_SELECT_CDF else None)

@@ -24,6 +24,10 @@ SMALL = {
     # text tokens appended to the video tokens (ragged last block, always-dense tail)
     "tiny_text": (inputs.Workload("tinytext", 13, 1, 2, 64, 6, 16, 16, 64, 0.5, 1, 0.3, text_tokens=40), {}),
     "image_text_d128": (inputs.Workload("imgtext", 14, 1, 2, 128, 1, 40, 36, 128, 0.5, 0, 0.3, text_tokens=77), {}),
+    # cumulative-mass selection: rows of different lengths
+    "tiny_cdf": (inputs.WORKLOADS["tiny"], dict(cdf_threshold=0.7)),
+    "ragged_cdf_d128": (inputs.Workload("raggedcdf", 15, 1, 3, 128, 5, 10, 13, 128, 0.5, 1, 0.3, text_tokens=9),
+                        dict(cdf_threshold=0.9)),
 }
 
 
@@ -82,12 +86,18 @@ def test_scores_and_block_mask(case):
         cnt = buf["blk_cnt"][0, h].cpu().numpy()
         sink = np.zeros(Tb, dtype=bool)
         sink[i.sink_block_begin:i.sink_block_end] = True
-        assert (cnt[sink] == Tb).all() and (cnt[~sink] == (i.k_row if i.k_row < Tb else Tb)).all()
-        assert M[:, sink].all() and M[sink].all()
-        clear = ref[h]["gap"] > hp.TIE_GAP
+        cdf = plan.cfg.select_mode == 1
+        assert (cnt[sink] == Tb).all() and M[:, sink].all() and M[sink].all()
+        clear = ref[h]["gap"] > (hp.CDF_TIE if cdf else hp.TIE_GAP)
         near_ties += int((~clear & ~sink).sum())
         assert np.array_equal(M[clear], ref[h]["M"][clear]), "mask differs on a row with a clear boundary"
-        assert (M.sum(1) == ref[h]["M"].sum(1)).all()
+        if cdf:                                     # a near-tie row may be one column longer or shorter
+            assert (cnt[~sink] == M[~sink].sum(1)).all() and (np.abs(M.sum(1) - ref[h]["M"].sum(1)) <= 1).all()
+            if (~sink).sum() >= 16:
+                assert len(set(cnt[~sink])) > 1, "cumulative-mass rows should differ in length on these inputs"
+        else:
+            assert (cnt[~sink] == (i.k_row if i.k_row < Tb else Tb)).all()
+            assert (M.sum(1) == ref[h]["M"].sum(1)).all()
     print(f"[mask] near-tie rows exempted: {near_ties}")
 
 

@@ -40,6 +40,7 @@ def make_plan(**kw):
     dict(batch=0), dict(heads=0), dict(T=0), dict(sink_frames=6), dict(sink_frames=-1), dict(sparsity=1.0),
     dict(sparsity=-0.1), dict(sparsity=float("nan")), dict(budget_mode=3), dict(window=(0, 4, 4)),
     dict(window=(-1, 4, 4)), dict(sink_at_end=2), dict(qkv_layout=2), dict(qkv_layout=-1), dict(text_tokens=-1),
+    dict(cdf_threshold=0.0), dict(cdf_threshold=1.0), dict(cdf_threshold=float("nan")),
 ])
 def test_invalid_configs_are_rejected(bad):
     with pytest.raises(rf2.Rf2Error) as e:
@@ -127,4 +128,11 @@ def test_text_tokens_tables_match_the_oracle(case):
     perm, inv = p.rf2_plan_perm()
     want = orc.perm_table(T, H, W, *win, sf, True, text)
     assert np.array_equal(perm, want) and np.array_equal(inv, orc.inverse_table(want))
+    p.close()
+
+
+def test_cdf_mode_reports_capacity_not_a_budget():
+    p = make_plan(cdf_threshold=0.8)
+    i = p.info
+    assert (i.k_row, i.k_sel, i.kept_pairs_per_head, i.achieved_sparsity) == (i.n_blocks, 0, -1, -1.0)
     p.close()
