@@ -1,0 +1,44 @@
+"""Diagnostic (CPU, oracle only): how much of the dense attention probability mass the predicted
+block mask keeps, with the window permutation of Sec. 3.3 and with plain raster-order blocks.
+
+This is the numeric stand-in for the paper's ablation of the 3-D permutation (its Sec. 4 shows
+images, not numbers).  The figures are printed; only properties that must hold are asserted."""
+import numpy as np
+import pytest
+
+from oracle import rf2_oracle as orc
+from paper_2512_24086_amd import inputs
+from tests import helpers as hp
+
+
+def mass_recall(Q, K, r, b):
+    """Mean over queries of the dense softmax mass that falls on kept blocks."""
+    N, d = Q.shape
+    inv = orc.inverse_table(r["perm"])
+    blk = inv // b
+    z = (Q @ K.T) / np.sqrt(d)
+    p = np.exp(z - z.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    keep = r["M"][blk][:, blk]
+    return float((p * keep).sum(axis=1).mean())
+
+
+@pytest.mark.parametrize("name,sparsity", [("tiny", 0.5), ("tiny", 0.7)])
+def test_recall_with_and_without_window_permutation(name, sparsity):
+    wl = inputs.WORKLOADS[name]
+    q, k, v = inputs.make_qkv(wl)
+    out = {}
+    for label, window in (("windows", None), ("raster", (1, 1, wl.block))):
+        rec = []
+        for h in range(wl.heads):
+            Q, K, V = (hp.f64(x[0, h]) for x in (q, k, v))
+            r = orc.layer(Q, K, V, T=wl.T, H=wl.H, W=wl.W, block=wl.block, sparsity=sparsity,
+                          sink_frames=wl.sink_frames, window=window)
+            rec.append(mass_recall(Q, K, r, wl.block))
+            assert 0.0 < rec[-1] <= 1.0 + 1e-12
+            kept = r["M"].sum() / r["M"].size
+        out[label] = float(np.mean(rec))
+    print(f"\n[recall] {name} s={sparsity}: kept density {kept:.3f}; attention mass kept with window blocks "
+          f"{out['windows']:.4f}, with raster blocks {out['raster']:.4f}")
+    dense = orc.layer(Q, K, V, T=wl.T, H=wl.H, W=wl.W, block=wl.block, sparsity=0.0, sink_frames=wl.sink_frames)
+    assert abs(mass_recall(Q, K, dense, wl.block) - 1.0) < 1e-12
