@@ -148,6 +148,8 @@ def main():
     ap.add_argument("--sparsity", type=float, default=None)
     ap.add_argument("--text-tokens", type=int, default=0,
                     help="append this many text tokens (always-dense rows and columns) to the video tokens")
+    ap.add_argument("--head-dim", type=int, default=None, choices=(64, 128), help="override the workload's head_dim")
+    ap.add_argument("--block", type=int, default=None, choices=(64, 128), help="override the workload's block size")
     ap.add_argument("--cdf", type=float, default=None,
                     help="cumulative-mass block selection with this threshold instead of top-n (row lengths vary)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -167,6 +169,8 @@ def main():
     wl = inputs.WORKLOADS[args.workload]
     if args.text_tokens:
         wl = dataclasses.replace(wl, text_tokens=args.text_tokens)
+    if args.head_dim or args.block:
+        wl = dataclasses.replace(wl, head_dim=args.head_dim or wl.head_dim, block=args.block or wl.block)
     s = wl.sparsity if args.sparsity is None else args.sparsity
     plan = rf2.Plan(batch=wl.batch, heads=wl.heads, head_dim=wl.head_dim, T=wl.T, H=wl.H, W=wl.W, block=wl.block,
                     sparsity=s, sink_frames=wl.sink_frames, text_tokens=wl.text_tokens, cdf_threshold=args.cdf)
@@ -217,7 +221,8 @@ def main():
                      "achieved": kept_flops / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": kept_flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                      "traffic": (ATTN_TRAFFIC_BYTES.get(wl.name)
-                                 if args.sparsity is None and not wl.text_tokens and args.cdf is None else None)},
+                                 if args.sparsity is None and not wl.text_tokens and args.cdf is None
+                                 and not args.head_dim and not args.block else None)},
     }
     if not args.no_dense:
         cnt_dense = torch.full_like(buf["blk_cnt"], i.n_blocks)

@@ -25,8 +25,10 @@ CASES = {
     "longvideo_s50": ("longvideo", 0.5, (5,)),
     # cumulative-mass selection with 512 text tokens: variable row lengths at full size
     "video720p_cdf_text": ("video720p", 0.8, (7,)),
+    # 64-token blocks: 1,182 blocks per head (the mask kernel's wide-row path), two wavefronts per workgroup
+    "video720p_b64": ("video720p", 0.8, (21,)),
 }
-EXTRA = {"video720p_cdf_text": dict(cdf_threshold=0.9, text_tokens=512)}
+EXTRA = {"video720p_cdf_text": dict(cdf_threshold=0.9, text_tokens=512), "video720p_b64": dict(block=64)}
 
 
 @pytest.fixture(scope="module", params=list(CASES), ids=list(CASES))
@@ -34,9 +36,11 @@ def big(request):
     name, s, heads = CASES[request.param]
     wl = inputs.WORKLOADS[name]
     extra = dict(EXTRA.get(request.param, {}))
+    import dataclasses
     if "text_tokens" in extra:
-        import dataclasses
         wl = dataclasses.replace(wl, text_tokens=extra.pop("text_tokens"))
+    if "block" in extra:
+        wl = dataclasses.replace(wl, block=extra.pop("block"))
     print(f"\n[case] {request.param}: {wl.name} N={wl.N} heads={wl.heads} sparsity={s} sampled heads {heads} {extra}",
           flush=True)
     plan = hp.make_plan(wl, sparsity=s, **extra)
