@@ -51,7 +51,8 @@ def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
 def default_window(block: int, video: bool) -> tuple[int, int, int]:
     """Window whose volume equals the block size, so one interior window is one
     block (the paper gives no shape; this is a parameter of the method)."""
-    table = {(128, True): (2, 8, 8), (128, False): (1, 8, 16),
+    table = {(256, True): (4, 8, 8), (256, False): (1, 16, 16),
+             (128, True): (2, 8, 8), (128, False): (1, 8, 16),
              (64, True): (4, 4, 4), (64, False): (1, 8, 8)}
     return table[(block, video)]
 
@@ -140,33 +141,38 @@ def sink_block_range(N: int, frame_tokens: int, b: int, sink_frames: int,
     return (0, -(-n_sink // b))
 
 
-def budget(Tb: int, n_sink_blocks: int, sparsity: float, mode: int = BUDGET_GLOBAL) -> tuple[int, int]:
-    """(k_row, k_sel): blocks kept per non-sink row in total, and those chosen
+def budget(Tb: int, n_sink_blocks: int, sparsity: float, mode: int = BUDGET_GLOBAL,
+           Tk: int | None = None, n_sink_k: int | None = None) -> tuple[int, int]:
+    """(k_row, k_sel): K blocks kept per non-sink row in total, and those chosen
     by score among the non-sink columns.  `sparsity` is taken as a float32
-    value; the arithmetic is IEEE double.
+    value; the arithmetic is IEEE double.  The mask has Tb rows (Q blocks, of
+    which n_sink_blocks are sink rows) and Tk columns (K blocks, n_sink_k sink
+    columns); by default it is square (Sec. 3.1 allows b_q != b_k).
 
-    GLOBAL: the target is the skipped fraction of the whole Tb x Tb mask, sink
-    rows and columns included.  ROW_INCL_SINK: each row keeps ceil((1-s)Tb)
-    blocks, the sink among them.  ROW_PLUS_SINK: each row selects ceil((1-s)Tb)
+    GLOBAL: the target is the skipped fraction of the whole Tb x Tk mask, sink
+    rows and columns included.  ROW_INCL_SINK: each row keeps ceil((1-s)Tk)
+    blocks, the sink among them.  ROW_PLUS_SINK: each row selects ceil((1-s)Tk)
     blocks on top of the sink."""
+    Tk = Tb if Tk is None else Tk
+    nSk = n_sink_blocks if n_sink_k is None else n_sink_k
     keep = 1.0 - float(np.float32(sparsity))
     nS = n_sink_blocks
     if nS >= Tb:
-        return (Tb, 0)
+        return (Tk, 0)
     if mode == BUDGET_GLOBAL:
-        k_row = int(math.floor((keep * Tb * Tb - float(nS) * Tb) / float(Tb - nS)))
+        k_row = int(math.floor((keep * Tb * Tk - float(nS) * Tk) / float(Tb - nS)))
     elif mode == BUDGET_ROW_INCL_SINK:
-        k_row = int(math.ceil(keep * Tb))
+        k_row = int(math.ceil(keep * Tk))
     elif mode == BUDGET_ROW_PLUS_SINK:
-        k_row = int(math.ceil(keep * Tb)) + nS
+        k_row = int(math.ceil(keep * Tk)) + nSk
     else:
         raise ValueError("budget mode")
-    k_row = min(max(k_row, nS, 1), Tb)
-    return (k_row, k_row - nS)
+    k_row = min(max(k_row, nSk, 1), Tk)
+    return (k_row, k_row - nSk)
 
 
-def kept_pairs(Tb: int, n_sink_blocks: int, k_row: int) -> int:
-    return (Tb - n_sink_blocks) * k_row + n_sink_blocks * Tb
+def kept_pairs(Tb: int, n_sink_blocks: int, k_row: int, Tk: int | None = None) -> int:
+    return (Tb - n_sink_blocks) * k_row + n_sink_blocks * (Tb if Tk is None else Tk)
 
 
 # --------------------------------------------------------------------------
@@ -184,33 +190,37 @@ def block_scores(qbar: np.ndarray, kbar: np.ndarray) -> np.ndarray:
     return qbar @ kbar.T
 
 
-def select_blocks(S_hat: np.ndarray, k_sel: int, sink_begin: int, sink_end: int) -> np.ndarray:
+def select_blocks(S_hat: np.ndarray, k_sel: int, sink_begin: int, sink_end: int, sink_k=None) -> np.ndarray:
     """Eq. (8) with the sink of Sec. 3.4.  Non-sink row i keeps the k_sel
     non-sink columns with the largest S_hat[i, :] (equal scores: lower column
-    first) and every sink column; sink rows keep every column."""
-    Tb = S_hat.shape[0]
-    M = np.zeros((Tb, Tb), dtype=bool)
-    cand = np.array([j for j in range(Tb) if not (sink_begin <= j < sink_end)], dtype=np.int64)
-    for i in range(Tb):
+    first) and every sink column; sink rows keep every column.  Rows are Q
+    blocks with sink range [sink_begin, sink_end); columns are K blocks with
+    sink range sink_k (the same range unless b_q != b_k)."""
+    Tq, Tk = S_hat.shape
+    kb, ke = (sink_begin, sink_end) if sink_k is None else sink_k
+    M = np.zeros((Tq, Tk), dtype=bool)
+    cand = np.array([j for j in range(Tk) if not (kb <= j < ke)], dtype=np.int64)
+    for i in range(Tq):
         if sink_begin <= i < sink_end:
             M[i, :] = True
             continue
         s = S_hat[i, cand]
         order = np.lexsort((cand, -s))          # by -score, then by column
         M[i, cand[order[:k_sel]]] = True
-        M[i, sink_begin:sink_end] = True
+        M[i, kb:ke] = True
     return M
 
 
-def selection_gap(S_hat: np.ndarray, k_sel: int, sink_begin: int, sink_end: int) -> np.ndarray:
+def selection_gap(S_hat: np.ndarray, k_sel: int, sink_begin: int, sink_end: int, sink_k=None) -> np.ndarray:
     """Per row: (k_sel-th largest candidate score) - ((k_sel+1)-th largest);
     +inf where the row has no boundary (sink row, or every candidate kept)."""
-    Tb = S_hat.shape[0]
-    cand = np.array([j for j in range(Tb) if not (sink_begin <= j < sink_end)], dtype=np.int64)
-    gap = np.full(Tb, np.inf)
+    Tq, Tk = S_hat.shape
+    kb, ke = (sink_begin, sink_end) if sink_k is None else sink_k
+    cand = np.array([j for j in range(Tk) if not (kb <= j < ke)], dtype=np.int64)
+    gap = np.full(Tq, np.inf)
     if k_sel <= 0 or k_sel >= cand.size:
         return gap
-    for i in range(Tb):
+    for i in range(Tq):
         if sink_begin <= i < sink_end:
             continue
         s = np.sort(S_hat[i, cand])[::-1]
@@ -218,7 +228,7 @@ def selection_gap(S_hat: np.ndarray, k_sel: int, sink_begin: int, sink_end: int)
     return gap
 
 
-def select_blocks_cdf(S_hat: np.ndarray, tau: float, d: int, sink_begin: int, sink_end: int):
+def select_blocks_cdf(S_hat: np.ndarray, tau: float, d: int, sink_begin: int, sink_end: int, sink_k=None):
     """Threshold variant of the selection (the cumulative-mass rule Sec. 2 describes for
     online adaptive patterns, applied to the block scores of eq. 7): for every non-sink
     row, softmax over the non-sink columns of S_hat / sqrt(d); the columns are taken in
@@ -231,11 +241,12 @@ def select_blocks_cdf(S_hat: np.ndarray, tau: float, d: int, sink_begin: int, si
     arithmetic of lower precision."""
     if not (0.0 < tau < 1.0):
         raise ValueError("tau must lie strictly between 0 and 1")
-    Tb = S_hat.shape[0]
-    M = np.zeros((Tb, Tb), dtype=bool)
-    margin = np.full(Tb, np.inf)
-    cand = np.array([j for j in range(Tb) if not (sink_begin <= j < sink_end)], dtype=np.int64)
-    for i in range(Tb):
+    Tq, Tk = S_hat.shape
+    kb, ke = (sink_begin, sink_end) if sink_k is None else sink_k
+    M = np.zeros((Tq, Tk), dtype=bool)
+    margin = np.full(Tq, np.inf)
+    cand = np.array([j for j in range(Tk) if not (kb <= j < ke)], dtype=np.int64)
+    for i in range(Tq):
         if sink_begin <= i < sink_end or cand.size == 0:
             M[i, :] = True
             continue
@@ -246,7 +257,7 @@ def select_blocks_cdf(S_hat: np.ndarray, tau: float, d: int, sink_begin: int, si
         cum = np.cumsum(p[order])
         n = int(np.argmax(cum >= tau)) + 1 if (cum >= tau).any() else cand.size
         M[i, cand[order[:n]]] = True
-        M[i, sink_begin:sink_end] = True
+        M[i, kb:ke] = True
         if n < cand.size:
             before = cum[n - 2] if n >= 2 else 0.0
             margin[i] = min(abs(cum[n - 1] - tau), abs(tau - before))
@@ -262,16 +273,19 @@ def mask_to_lists(M: np.ndarray) -> list[np.ndarray]:
 # Sec. 3.1: block-sparse flash attention, eqs. (1)-(4) + skip rule
 # --------------------------------------------------------------------------
 def block_sparse_attention(Qp: np.ndarray, Kp: np.ndarray, Vp: np.ndarray, M: np.ndarray,
-                           b: int, q_blocks=None, return_lse: bool = False):
+                           b: int, q_blocks=None, return_lse: bool = False, bk: int | None = None):
     """Output rows of the requested Q blocks (default: all), by the online
-    recurrences: for each kept block j in ascending order
+    recurrences (Q blocks of b rows, K/V blocks of bk rows, bk = b unless
+    given; M is [ceil(N/b), ceil(N/bk)]): for each kept block j in ascending order
         S = Q_i K_j^T / sqrt(d)                                   (1)
         m_new = max(m, rowmax S),  P = exp(S - m_new)             (2)
         l = exp(m - m_new) l + rowsum P                           (3)
         O = diag(exp(m - m_new)) O + P V_j                        (4)
     and finally O_i = diag(l)^-1 O.  Blocks with M[i, j] == 0 are skipped."""
     N, d = Qp.shape
-    Tb = n_blocks(N, b)
+    bk = b if bk is None else bk
+    Tb, Tk = n_blocks(N, b), n_blocks(N, bk)
+    assert M.shape == (Tb, Tk)
     rows = range(Tb) if q_blocks is None else q_blocks
     dv = Vp.shape[1]
     O = np.zeros((N, dv))
@@ -283,10 +297,10 @@ def block_sparse_attention(Qp: np.ndarray, Kp: np.ndarray, Vp: np.ndarray, M: np
         m = np.full((Qi.shape[0], 1), -np.inf)
         l = np.zeros((Qi.shape[0], 1))
         acc = np.zeros((Qi.shape[0], dv))
-        for j in range(Tb):
+        for j in range(Tk):
             if not M[i, j]:
                 continue
-            ks = block_slice(j, N, b)
+            ks = block_slice(j, N, bk)
             S = (Qi @ Kp[ks].T) * inv_sqrt_d
             m_new = np.maximum(m, S.max(axis=1, keepdims=True))
             P = np.exp(S - m_new)
@@ -310,7 +324,7 @@ def block_sparse_attention(Qp: np.ndarray, Kp: np.ndarray, Vp: np.ndarray, M: np
 def layer(Q: np.ndarray, K: np.ndarray, V: np.ndarray, *, T: int, H: int, W: int, block: int,
           sparsity: float, sink_frames: int = 0, sink_at_end: bool = True,
           window=None, budget_mode: int = BUDGET_GLOBAL, q_blocks=None, text_tokens: int = 0,
-          cdf_threshold: float | None = None) -> dict:
+          cdf_threshold: float | None = None, block_k: int | None = None) -> dict:
     """All stages for one (batch, head).  Q, K, V: [N, d] float64, the video
     tokens in [T,H,W] raster order followed by `text_tokens` text tokens.
     Returns every intermediate."""
@@ -319,19 +333,21 @@ def layer(Q: np.ndarray, K: np.ndarray, V: np.ndarray, *, T: int, H: int, W: int
     wt, wh, ww = window if window is not None else default_window(block, T > 1)
     perm = perm_table(T, H, W, wt, wh, ww, sink_frames, sink_at_end, text_tokens)
     Qp, Kp, Vp = permute(Q, perm), permute(K, perm), permute(V, perm)
-    qbar, kbar = pool_blocks(Qp, block), pool_blocks(Kp, block)
+    bk = block if block_k is None else block_k            # Q blocks of `block` rows, K/V blocks of bk rows
+    qbar, kbar = pool_blocks(Qp, block), pool_blocks(Kp, bk)
     S_hat = block_scores(qbar, kbar)
-    Tb = n_blocks(N, block)
+    Tb, Tk = n_blocks(N, block), n_blocks(N, bk)
     sb, se = sink_block_range(N, H * W, block, sink_frames, sink_at_end, text_tokens)
-    k_row, k_sel = budget(Tb, se - sb, sparsity, budget_mode)
+    sink_k = sink_block_range(N, H * W, bk, sink_frames, sink_at_end, text_tokens)
+    k_row, k_sel = budget(Tb, se - sb, sparsity, budget_mode, Tk, sink_k[1] - sink_k[0])
     if cdf_threshold is None:
-        M = select_blocks(S_hat, k_sel, sb, se)
-        gap = selection_gap(S_hat, k_sel, sb, se)
+        M = select_blocks(S_hat, k_sel, sb, se, sink_k)
+        gap = selection_gap(S_hat, k_sel, sb, se, sink_k)
     else:                       # cumulative-mass selection: row lengths vary, the budget does not apply
-        M, gap = select_blocks_cdf(S_hat, cdf_threshold, Q.shape[1], sb, se)
-        k_row, k_sel = Tb, 0
-    Op, lse = block_sparse_attention(Qp, Kp, Vp, M, block, q_blocks=q_blocks, return_lse=True)
+        M, gap = select_blocks_cdf(S_hat, cdf_threshold, Q.shape[1], sb, se, sink_k)
+        k_row, k_sel = Tk, 0
+    Op, lse = block_sparse_attention(Qp, Kp, Vp, M, block, q_blocks=q_blocks, return_lse=True, bk=bk)
     O = unpermute(Op, perm)
     return dict(perm=perm, Qp=Qp, Kp=Kp, Vp=Vp, qbar=qbar, kbar=kbar, S_hat=S_hat, M=M,
-                sink=(sb, se), k_row=k_row, k_sel=k_sel, Op=Op, lse=lse, O=O,
+                sink=(sb, se), sink_k=sink_k, k_row=k_row, k_sel=k_sel, Op=Op, lse=lse, O=O,
                 gap=gap)

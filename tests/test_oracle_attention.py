@@ -164,3 +164,26 @@ def test_layer_with_text_tokens():
     im = orc.layer(Q[H * W * 3:], K[H * W * 3:], V[H * W * 3:], T=1, H=H, W=W, block=b, sparsity=0.5,
                    window=(1, 4, 8), text_tokens=text)
     assert im["sink"] == (2, 3) and im["M"][:, 2].all() and im["M"][2].all()
+
+
+@pytest.mark.parametrize("bq,bk", [(32, 16), (16, 32), (64, 16)])
+def test_layer_with_different_q_and_k_blocks(bq, bk):
+    """b_q != b_k (Sec. 3.1): the whole layer equals library masked attention whose token-level mask is
+    built from the Q block of the query and the K block of the key; sink rows/columns are dense; with
+    every block kept it is plain attention."""
+    rng = np.random.default_rng(bq * 100 + bk)
+    T, H, W, d = 4, 8, 8, 8
+    N = T * H * W
+    Q, K, V = (_smooth(rng, T, H, W, d) for _ in range(3))
+    r = orc.layer(Q, K, V, T=T, H=H, W=W, block=bq, block_k=bk, sparsity=0.5, sink_frames=1, window=(1, 4, 8))
+    Tq, Tk = N // bq, N // bk
+    assert r["M"].shape == (Tq, Tk) and r["qbar"].shape[0] == Tq and r["kbar"].shape[0] == Tk
+    (sb, se), (kb, ke) = r["sink"], r["sink_k"]
+    assert (se, ke) == (Tq, Tk) and sb * bq == kb * bk == 3 * H * W       # body = 3 frames, block aligned here
+    assert r["M"][sb:].all() and r["M"][:, kb:].all() and (r["M"][:sb].sum(1) == r["k_row"]).all()
+    assert 1.0 - r["M"].sum() / r["M"].size >= 0.5
+    inv = orc.inverse_table(r["perm"])
+    allow = r["M"][inv // bq][:, inv // bk]
+    assert np.abs(r["O"] - sdpa_f64(Q, K, V, allow)).max() < 1e-12
+    dense = orc.layer(Q, K, V, T=T, H=H, W=W, block=bq, block_k=bk, sparsity=0.0, sink_frames=1, window=(2, 4, 4))
+    assert dense["M"].all() and np.abs(dense["O"] - sdpa_f64(Q, K, V)).max() < 1e-12

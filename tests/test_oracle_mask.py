@@ -181,3 +181,38 @@ def test_layer_with_cdf_selection_equals_library_masked_attention():
     allow = torch.from_numpy(r["M"][inv // b][:, inv // b])
     want = torch.nn.functional.scaled_dot_product_attention(*(torch.from_numpy(x)[None] for x in X), attn_mask=allow[None])[0]
     assert np.abs(r["O"] - want.numpy()).max() < 1e-12
+
+
+def test_rectangular_selection_vs_brute_force():
+    """Different block sizes for Q and K: the mask is Tq x Tk with separate sink ranges."""
+    rng = np.random.default_rng(31)
+    Tq, Tk, k_sel = 7, 13, 4
+    S = rng.standard_normal((Tq, Tk))
+    rows, cols = (5, 7), (10, 13)
+    M = orc.select_blocks(S, k_sel, *rows, sink_k=cols)
+    gap = orc.selection_gap(S, k_sel, *rows, sink_k=cols)
+    for i in range(Tq):
+        if rows[0] <= i < rows[1]:
+            assert M[i].all() and gap[i] == np.inf
+            continue
+        cand = sorted(range(cols[0]), key=lambda j: (-S[i, j], j))
+        want = set(cand[:k_sel]) | set(range(*cols))
+        assert set(np.flatnonzero(M[i])) == want
+        assert abs(gap[i] - (S[i, cand[k_sel - 1]] - S[i, cand[k_sel]])) < 1e-15
+    Mc, _ = orc.select_blocks_cdf(S * 5, 0.6, 16, *rows, sink_k=cols)
+    assert Mc.shape == (Tq, Tk) and Mc[:, 10:].all() and Mc[5:].all()
+    assert np.array_equal(Mc[:5], _cdf_by_loops_rect(S * 5, 0.6, 16, cols)[:5])
+
+
+def _cdf_by_loops_rect(S, tau, d, cols):
+    M = np.zeros(S.shape, dtype=bool)
+    for i in range(S.shape[0]):
+        cand = list(range(cols[0]))
+        w = {j: np.exp(S[i, j] / np.sqrt(d)) for j in cand}
+        total, taken, mass = sum(w.values()), [], 0.0
+        while cand and (not taken or mass < tau * total):
+            best = max(cand, key=lambda j: (S[i, j], -j))
+            cand.remove(best); taken.append(best); mass += w[best]
+        M[i, taken] = True
+        M[i, cols[0]:cols[1]] = True
+    return M

@@ -175,3 +175,20 @@ def test_bf16_decoding():
     got = orc.bf16_bits_to_f64(bits)
     assert got[:3].tolist() == [1.0, -1.0, 2.0]
     assert got[3] == 0.10009765625 and got[4] == 0.0 and np.isinf(got[5])
+
+
+@pytest.mark.parametrize("row", list(_rows("config_sizes_rect.txt")), ids=lambda r: r[0])
+def test_sizes_with_different_q_and_k_blocks(row):
+    _, thw, bqk, sf, s, N, tqk, sq, sk, kk, kept = row
+    T, H, W = map(int, thw.split())
+    bq, bk = map(int, bqk.split())
+    Tq, Tk = map(int, tqk.split())
+    (sbq, nSq), (sbk, nSk) = map(int, sq.split()), map(int, sk.split())
+    k_row, k_sel = map(int, kk.split())
+    N = int(N)
+    assert T * H * W == N and (orc.n_blocks(N, bq), orc.n_blocks(N, bk)) == (Tq, Tk)
+    assert orc.sink_block_range(N, H * W, bq, int(sf), True) == (sbq, sbq + nSq) == (sbq, Tq)
+    assert orc.sink_block_range(N, H * W, bk, int(sf), True) == (sbk, sbk + nSk) == (sbk, Tk)
+    assert orc.budget(Tq, nSq, float(s), orc.BUDGET_GLOBAL, Tk, nSk) == (k_row, k_sel)
+    assert orc.kept_pairs(Tq, nSq, k_row, Tk) == int(kept)
+    assert 1.0 - int(kept) / (Tq * Tk) >= float(s) - 1e-9
