@@ -114,16 +114,18 @@ def cpu_baseline(wl, plan, q, k, v, dense_flops):
     t0 = time.perf_counter()
     perm = orc.perm_table(c.T, c.H, c.W, i.wt, i.wh, i.ww, c.sink_frames, bool(c.sink_at_end), c.text_tokens)
     Qp, Kp, Vp = orc.permute(Q, perm), orc.permute(K, perm), orc.permute(V, perm)
-    S_hat = orc.block_scores(orc.pool_blocks(Qp, c.block), orc.pool_blocks(Kp, c.block))
+    S_hat = orc.block_scores(orc.pool_blocks(Qp, c.block), orc.pool_blocks(Kp, i.block_k))
+    sink_k = (i.sink_block_begin_k, i.sink_block_end_k)
     if c.select_mode == rf2.RF2_SELECT_CDF:
-        M, _ = orc.select_blocks_cdf(S_hat, float(c.cdf_threshold), c.head_dim, i.sink_block_begin, i.sink_block_end)
+        M, _ = orc.select_blocks_cdf(S_hat, float(c.cdf_threshold), c.head_dim, i.sink_block_begin, i.sink_block_end,
+                                     sink_k)
     else:
-        M = orc.select_blocks(S_hat, i.k_sel, i.sink_block_begin, i.sink_block_end)
+        M = orc.select_blocks(S_hat, i.k_sel, i.sink_block_begin, i.sink_block_end, sink_k)
     t_pre = time.perf_counter() - t0
     Tb = i.n_blocks
     sample = list(range(Tb))                           # every Q block of this one head: ~10 s of oracle time
     t0 = time.perf_counter()
-    Op = orc.block_sparse_attention(Qp, Kp, Vp, M, c.block, q_blocks=sample)
+    Op = orc.block_sparse_attention(Qp, Kp, Vp, M, c.block, q_blocks=sample, bk=i.block_k)
     t_attn = time.perf_counter() - t0
     pairs = int(sum(M[r].sum() for r in sample))
     t_unp0 = time.perf_counter()
@@ -149,7 +151,9 @@ def main():
     ap.add_argument("--text-tokens", type=int, default=0,
                     help="append this many text tokens (always-dense rows and columns) to the video tokens")
     ap.add_argument("--head-dim", type=int, default=None, choices=(64, 128), help="override the workload's head_dim")
-    ap.add_argument("--block", type=int, default=None, choices=(64, 128), help="override the workload's block size")
+    ap.add_argument("--block", type=int, default=None, choices=(64, 128, 256),
+                    help="override the workload's block size (b_q; also b_k unless --block-k is given)")
+    ap.add_argument("--block-k", type=int, default=0, choices=(0, 64, 128), help="K/V block size b_k if different")
     ap.add_argument("--cdf", type=float, default=None,
                     help="cumulative-mass block selection with this threshold instead of top-n (row lengths vary)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -173,7 +177,8 @@ def main():
         wl = dataclasses.replace(wl, head_dim=args.head_dim or wl.head_dim, block=args.block or wl.block)
     s = wl.sparsity if args.sparsity is None else args.sparsity
     plan = rf2.Plan(batch=wl.batch, heads=wl.heads, head_dim=wl.head_dim, T=wl.T, H=wl.H, W=wl.W, block=wl.block,
-                    sparsity=s, sink_frames=wl.sink_frames, text_tokens=wl.text_tokens, cdf_threshold=args.cdf)
+                    sparsity=s, sink_frames=wl.sink_frames, text_tokens=wl.text_tokens, cdf_threshold=args.cdf,
+                    block_k=args.block_k)
     i = plan.info
     q, k, v = inputs.make_qkv(wl, device="cuda")
     buf = plan.alloc("cuda")
@@ -186,7 +191,7 @@ def main():
     kept_pairs = i.kept_pairs_per_head * bh
     if args.cdf is not None:            # data dependent: count what the mask kernel kept
         kept_pairs = int(buf["blk_cnt"].sum().item())
-    kept_flops = 4.0 * wl.block * wl.block * wl.head_dim * kept_pairs
+    kept_flops = 4.0 * wl.block * i.block_k * wl.head_dim * kept_pairs
     attn_ms = stages["block_sparse_attn"]
     itemsize = 2
     tensor_bytes = bh * wl.N * wl.head_dim * itemsize
@@ -203,10 +208,12 @@ def main():
         "config": {"workload": f"{wl.name}: B{wl.batch} x {wl.heads} heads x d{wl.head_dim}, grid {wl.T}x{wl.H}x{wl.W}"
                                f" = {wl.T * wl.H * wl.W} tokens"
                                + (f" + {wl.text_tokens} text tokens" if wl.text_tokens else "")
-                               + f", block {wl.block}, sparsity {s}, sink_frames {wl.sink_frames}",
+                               + f", block {wl.block}" + (f" (K/V blocks {i.block_k})" if i.block_k != wl.block else "")
+                               + f", sparsity {s}, sink_frames {wl.sink_frames}",
                    "selection": "top-n (eq. 8)" if args.cdf is None else f"cumulative mass >= {args.cdf}",
-                   "n_blocks": i.n_blocks, "k_row": i.k_row, "kept_pairs_per_head": kept_pairs / bh,
-                   "achieved_sparsity": round(1.0 - kept_pairs / bh / i.n_blocks ** 2, 4),
+                   "n_blocks": i.n_blocks, "n_blocks_k": i.n_blocks_k, "k_row": i.k_row,
+                   "kept_pairs_per_head": kept_pairs / bh,
+                   "achieved_sparsity": round(1.0 - kept_pairs / bh / (i.n_blocks * i.n_blocks_k), 4),
                    "inverse_permutation": "rf2_unpermute" if args.unfused else "fused into the attention epilogue"},
         "stages_ms": {n: round(t, 4) for n, t in stages.items()},
         "stages_ms_median_min": {n: [round(v["median"], 4), round(v["min"], 4)] for n, v in spread.items()
@@ -222,10 +229,10 @@ def main():
                      "frac": kept_flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                      "traffic": (ATTN_TRAFFIC_BYTES.get(wl.name)
                                  if args.sparsity is None and not wl.text_tokens and args.cdf is None
-                                 and not args.head_dim and not args.block else None)},
+                                 and not args.head_dim and not args.block and not args.block_k else None)},
     }
     if not args.no_dense:
-        cnt_dense = torch.full_like(buf["blk_cnt"], i.n_blocks)
+        cnt_dense = torch.full_like(buf["blk_cnt"], i.n_blocks_k)
         dense_ms = time_attn_only(plan, buf, buf["blk_idx"], cnt_dense, iters=2)
         sdpa_ms = time_sdpa(q, k, v)
         best = min(dense_ms, sdpa_ms) if isinstance(sdpa_ms, float) else dense_ms

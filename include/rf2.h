@@ -76,7 +76,7 @@ typedef struct {
   int32_t T, H, W;                /* latent grid (frames, height, width); T = 1 for an image */
   int32_t wt, wh, ww;             /* window of the Sec. 3.3 permutation; all three 0 = default:
                                      b=128: video (2,8,8), image (1,8,16); b=64: video (4,4,4), image (1,8,8) */
-  int32_t block;                  /* b in {64, 128} */
+  int32_t block;                  /* b_q, rows of a Q block, in {64, 128, 256}; also b_k unless block_k is set */
   int32_t sink_frames;            /* leading frames treated as the Sec. 3.4 sink: 0 or more, < T */
   int32_t sink_at_end;            /* 1: sink tokens placed after the body (Sec. 3.4, last paragraph); 0: before */
   float sparsity;                 /* target s in [0, 1) */
@@ -90,20 +90,32 @@ typedef struct {
                                      >= 0; with text_tokens > 0 the sink frames must be at the end. */
   int32_t select_mode;            /* RF2_SELECT_* */
   float cdf_threshold;            /* tau of RF2_SELECT_CDF, strictly between 0 and 1; ignored otherwise */
+  int32_t block_k;                /* b_k, rows of a K/V block, in {64, 128}; 0 = same as `block` (Sec. 3.1 lets
+                                     b_q and b_k differ).  The block mask then has ceil(N/b_q) rows and
+                                     ceil(N/b_k) columns; a larger b_q means fewer, longer Q rows that share
+                                     one K list (less K/V traffic per query), a coarser prediction. */
 } rf2_config;
 
 typedef struct {
-  int64_t N, N_pad;         /* N = T*H*W + text_tokens; N_pad = n_blocks * block */
-  int32_t n_blocks;         /* Tb */
-  int32_t last_block_valid; /* tokens in the last block, 1..b */
+  int64_t N, N_pad;         /* N = T*H*W + text_tokens; N_pad = n_blocks * block (rows of qp and op) */
+  int32_t n_blocks;         /* Tb = Tq: Q blocks = rows of the block mask */
+  int32_t last_block_valid; /* tokens in the last Q block, 1..b_q */
   int32_t sink_block_begin, sink_block_end; /* [begin, end) of blocks holding >= 1 sink-frame or text token;
                                                equal if none */
-  int32_t k_row;            /* blocks kept by every non-sink row, sink blocks included */
+  int32_t k_row;            /* K blocks kept by every non-sink row, sink blocks included */
   int32_t k_sel;            /* of those, chosen by score among non-sink columns = k_row - (end - begin) */
   int32_t wt, wh, ww;       /* window actually used */
   int64_t kept_pairs_per_head;
-  double achieved_sparsity; /* 1 - kept_pairs_per_head / Tb^2 */
+  double achieved_sparsity; /* 1 - kept_pairs_per_head / (Tq * Tk) */
   int64_t workspace_bytes;  /* size rf2_predict_mask needs at `workspace` (currently 0) */
+  /* K side of the block mask; equal to the Q side unless block_k differs from block.  Wherever the
+     entry points below say Tb for a COLUMN count (list entries, blk_cnt == Tb, kp/vp/kbar, the columns of
+     mask_dense and scores) it is n_blocks_k, and b there is block_k. */
+  int32_t block_k;            /* b_k actually used */
+  int32_t n_blocks_k;         /* Tk = ceil(N / b_k) */
+  int32_t last_block_valid_k; /* tokens in the last K block, 1..b_k */
+  int32_t sink_block_begin_k, sink_block_end_k; /* K blocks holding >= 1 sink-frame or text token */
+  int64_t N_pad_k;            /* n_blocks_k * block_k (rows of kp and vp) */
 } rf2_info;
 
 typedef struct rf2_plan rf2_plan; /* opaque */
@@ -119,7 +131,7 @@ typedef struct rf2_plan rf2_plan; /* opaque */
  * precede the body; text tokens come last, in their own order.  *out receives a plan to be released with rf2_plan_destroy.
  * If the process sees no HIP device the plan is host-only: rf2_plan_info and
  * rf2_plan_perm work, every compute call returns RF2_ERR_HIP.
- * Limits: N <= 2^24, Tb <= 2048, B*Hh <= 65535 (RF2_ERR_UNSUPPORTED beyond).
+ * Limits: N <= 2^24, Tq and Tk <= 2048, B*Hh <= 65535 (RF2_ERR_UNSUPPORTED beyond).
  */
 int rf2_plan_create(const rf2_config* cfg, rf2_plan** out);
 int rf2_plan_destroy(rf2_plan* plan);
@@ -132,6 +144,7 @@ int rf2_plan_perm(const rf2_plan* plan, int32_t* perm_host, int32_t* inv_host);
  *   q, k, v : [B, Hh, N, d] (or [B, N, Hh, d], see qkv_layout) bf16, tokens in
  *             [T, H, W] raster order                                       (in)
  *   qp      : [B, Hh, N_pad, d] bf16, qp[p] = q[perm[p]]; rows >= N zero  (out)
+ *   (below, b = block_k and Tb = n_blocks_k: K and V are cut into K/V blocks)
  *   kp      : [B, Hh, Tb, b/64, d/8, 64, 8] bf16 operand tiles.  With KH = b/2, channel
  *             8c+e of the permuted key row blk*b + r is element
  *                 (blk, part = (r % KH) / 32, c, (r / KH)*32 + r % 32, e);

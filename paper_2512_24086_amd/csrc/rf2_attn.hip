@@ -1,7 +1,7 @@
 // Block-sparse flash attention (Sec. 3.1, eqs. 1-4 with the block skip rule) for gfx950.
 //
-// One workgroup owns one Q block (BLK rows) of one (batch, head) and walks that row's list of
-// kept K/V blocks.  Every wavefront owns 32 query rows and sees all keys, so there is nothing
+// One workgroup owns one Q block (b_q rows) of one (batch, head) and walks that row's list of
+// kept K/V blocks (b_k rows each; b_q and b_k may differ).  Every wavefront owns 32 query rows and sees all keys, so there is nothing
 // to merge at the end; a workgroup needs at most 80 KiB of LDS and 256 registers per lane, so
 // two workgroups share a compute unit (two wavefronts per SIMD) and each hides the barriers,
 // LDS latencies and vector-ALU phases of the other.
@@ -38,16 +38,17 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-template <int D, int BLK>
+// BQ rows per Q block (one workgroup), BK rows per K/V block (Sec. 3.1: b_q and b_k).
+template <int D, int BQ, int BK>
 struct AttnCfg {
-  static constexpr int NW = BLK / 32;           // wavefronts, 32 query rows each
+  static constexpr int NW = BQ / 32;            // wavefronts, 32 query rows each
   static constexpr int NT = NW * 64;
-  static constexpr int KH = BLK / 2;            // block rows r and r + KH share a part (see rf2.h)
-  static constexpr int PB = BLK / 64;           // 64-key parts per block
-  static constexpr int UB = BLK / 32;           // 32-key units per block
+  static constexpr int KH = BK / 2;             // K block rows r and r + KH share a part (see rf2.h)
+  static constexpr int PB = BK / 64;            // 64-key parts per K/V block
+  static constexpr int UB = BK / 32;            // 32-key units per K/V block
   static constexpr int DS = D / 16;             // k-steps of the first product
   static constexpr int DT = D / 32;             // 32-channel tiles of the output
-  static constexpr int TILE_BYTES = BLK * D * 2;
+  static constexpr int TILE_BYTES = BK * D * 2;
   static constexpr int PART_BYTES = 64 * D * 2;
   static constexpr int LPW = PART_BYTES / 1024 / NW;   // 1 KiB direct-to-LDS loads per wavefront per part
   static constexpr int NK = 3, NV = 2;                 // ring depths in parts
@@ -120,16 +121,19 @@ __device__ __forceinline__ void ring_barrier() {
   asm volatile("" ::: "memory");
 }
 
-// (second launch bound: wavefronts per SIMD the register budget is sized for; a 64-row block has only
-// two wavefronts per workgroup, which LDS limits to one per SIMD anyway)
-template <int D, int BLK>
-__global__ void __launch_bounds__(BLK * 2, BLK >= 128 ? 2 : 1) block_sparse_attn_kernel(
+// (second launch bound: wavefronts per SIMD the register budget is sized for; a 64-row Q block has only
+// two wavefronts per workgroup, which LDS limits to one per SIMD anyway; a 256-row Q block is one
+// workgroup of eight wavefronts per compute unit)
+template <int D, int BQ, int BK>
+__global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_kernel(
     const __bf16* __restrict__ qp, const __bf16* __restrict__ kp, const __bf16* __restrict__ vp,
     const int32_t* __restrict__ blk_idx, const int32_t* __restrict__ blk_cnt, __bf16* __restrict__ op,
     float* __restrict__ lse, const int32_t* __restrict__ row_order, int sink_per_xcd, int plain_per_xcd, int n_bh,
-    int Tb, int k_row, int last_valid, float scale_log2, const int32_t* __restrict__ scatter, int n_tokens,
+    int Tq, int Tb, int k_row, int last_valid, float scale_log2, const int32_t* __restrict__ scatter, int n_tokens,
     int heads, rf2_strides st) {
-  using C = AttnCfg<D, BLK>;
+  // Tq: Q blocks per head (rows of the block mask); Tb: K/V blocks per head (its columns); last_valid:
+  // tokens in the last K/V block.
+  using C = AttnCfg<D, BQ, BK>;
   // Part P lives in slot P % NK of the K ring (first) and slot P % NV of the V^T ring (behind it).
   __shared__ __attribute__((aligned(1024))) unsigned char ring[(C::NK + C::NV) * C::PART_BYTES];
   constexpr uint32_t VRING = C::NK * C::PART_BYTES;
@@ -162,7 +166,7 @@ __global__ void __launch_bounds__(BLK * 2, BLK >= 128 ? 2 : 1) block_sparse_attn
   // collects the large shares of every head.
   const int qi = row_order[((xcd + bh) & 7) * (sink_per_xcd + plain_per_xcd) + entry];
   if (qi < 0) return;
-  const size_t row_id = (size_t)bh * Tb + qi;
+  const size_t row_id = (size_t)bh * Tq + qi;
   int cnt = blk_cnt[row_id];
   const bool dense = (cnt == Tb);
   cnt = dense ? Tb : min(max(cnt, 0), k_row);
@@ -174,9 +178,10 @@ __global__ void __launch_bounds__(BLK * 2, BLK >= 128 ? 2 : 1) block_sparse_attn
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in a scalar register
   const uint32_t tid16 = (uint32_t)tid * 16u;
   const int l32 = lane & 31, lh = lane >> 5;
-  const size_t head_off = (size_t)bh * Tb * BLK * D;    // elements; same for qp, kp, vp, op
-  const unsigned char* const kbase = uniform_ptr(kp + head_off);
-  const unsigned char* const vbase = uniform_ptr(vp + head_off);
+  const size_t q_head_off = (size_t)bh * Tq * BQ * D;   // elements; qp and op
+  const size_t k_head_off = (size_t)bh * Tb * BK * D;   // kp and vp
+  const unsigned char* const kbase = uniform_ptr(kp + k_head_off);
+  const unsigned char* const vbase = uniform_ptr(vp + k_head_off);
   // LDS byte offsets of this lane's first operand chunk inside a K part / a V^T part, for the
   // first 32-key tile of the part; the second tile lies K_TILE / V_TILE bytes further.
   const uint32_t k_lane = (uint32_t)((lh * 64 + l32) * 16);
@@ -198,7 +203,7 @@ __global__ void __launch_bounds__(BLK * 2, BLK >= 128 ? 2 : 1) block_sparse_attn
   const uint32_t ring_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)ring;
   // Only the last listed block can be the ragged last block of the sequence (lists ascend).
   int partial_begin = U;
-  if (U > 0 && last_valid < BLK) {
+  if (U > 0 && last_valid < BK) {
     const int jl = dense ? cnt - 1 : list[cnt - 1];
     if (min(max(jl, 0), Tb - 1) == Tb - 1) partial_begin = (cnt - 1) * C::UB;
   }
@@ -401,7 +406,7 @@ __global__ void __launch_bounds__(BLK * 2, BLK >= 128 ? 2 : 1) block_sparse_attn
     // the slot of "part -1" (read by step 0 with zero probabilities) gets finite data
     dma_part<C::NW, C::LPW>(ring + VRING + (C::NV - 1) * C::PART_BYTES, vbase + part_at(0), wave, tid16);
     {
-      const __bf16* qrow = qp + head_off + ((size_t)qi * BLK + 32 * wave + l32) * D + 8 * lh;
+      const __bf16* qrow = qp + q_head_off + ((size_t)qi * BQ + 32 * wave + l32) * D + 8 * lh;
 #pragma unroll
       for (int ds = 0; ds < C::DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ds);
     }
@@ -455,12 +460,12 @@ __global__ void __launch_bounds__(BLK * 2, BLK >= 128 ? 2 : 1) block_sparse_attn
   const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
   const float l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
   const float f = l_tot > 0.f ? 1.0f / l_tot : 0.f;      // a row with no kept key yields zeros
-  const size_t row = (size_t)qi * BLK + 32 * wave + l32;
+  const size_t row = (size_t)qi * BQ + 32 * wave + l32;
   // plain output: row `row` of the permuted layout; fused inverse permutation: the token's raster row
   const int target = scatter ? scatter[row] : (int)row;
   if (target < 0) return;                                 // padding row of the last block
   __bf16* orow = scatter ? op + ((bh / heads) * st.batch + (bh % heads) * st.head + (long long)target * st.token) * D
-                         : op + head_off + row * D;
+                         : op + q_head_off + row * D;
 #pragma unroll
   for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
@@ -471,37 +476,50 @@ __global__ void __launch_bounds__(BLK * 2, BLK >= 128 ? 2 : 1) block_sparse_attn
       *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g + 4 * lh) = pk;
     }
   if (lse != nullptr && lh == 0)
-    lse[scatter ? (size_t)bh * n_tokens + target : (size_t)bh * Tb * BLK + row] =
+    lse[scatter ? (size_t)bh * n_tokens + target : (size_t)bh * Tq * BQ + row] =
         m_ref * scale_log2 * 0.6931471805599453f + __logf(l_tot);
 }
 
-template <int D, int BLK>
+template <int D, int BQ, int BK>
 int launch_attn(const rf2_plan* plan, const void* qp, const void* kp, const void* vp, const int32_t* blk_idx,
                 const int32_t* blk_cnt, void* op, float* lse, bool scatter, hipStream_t st) {
-  using C = AttnCfg<D, BLK>;
+  using C = AttnCfg<D, BQ, BK>;
   const rf2_config& c = plan->cfg;
   const rf2_info& in = plan->info;
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
   const int n_bh = c.batch * c.heads;
   const unsigned grid = 8u * (unsigned)(plan->sink_per_xcd + plan->plain_per_xcd) * (unsigned)n_bh;
-  block_sparse_attn_kernel<D, BLK><<<dim3(grid), dim3(C::NT), 0, st>>>(
+  block_sparse_attn_kernel<D, BQ, BK><<<dim3(grid), dim3(C::NT), 0, st>>>(
       (const __bf16*)qp, (const __bf16*)kp, (const __bf16*)vp, blk_idx, blk_cnt, (__bf16*)op, lse, plan->d_row_order,
-      plan->sink_per_xcd, plan->plain_per_xcd, n_bh, in.n_blocks, in.k_row, in.last_block_valid, scale_log2,
-      scatter ? plan->d_perm : nullptr, (int)in.N, c.heads, rf2_qkv_strides(plan));
+      plan->sink_per_xcd, plan->plain_per_xcd, n_bh, in.n_blocks, in.n_blocks_k, in.k_row, in.last_block_valid_k,
+      scale_log2, scatter ? plan->d_perm : nullptr, (int)in.N, c.heads, rf2_qkv_strides(plan));
   RF2_LAUNCH_CHECK();
   return RF2_OK;
+}
+
+template <int D>
+int dispatch_blocks(const rf2_plan* plan, const void* qp, const void* kp, const void* vp, const int32_t* blk_idx,
+                    const int32_t* blk_cnt, void* out, float* lse, bool scatter, hipStream_t st) {
+  const int bq = plan->cfg.block, bk = plan->info.block_k;
+#define RF2_ATTN_CASE(Q, K) \
+  if (bq == Q && bk == K) return launch_attn<D, Q, K>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
+  RF2_ATTN_CASE(128, 128)
+  RF2_ATTN_CASE(64, 64)
+  RF2_ATTN_CASE(128, 64)
+  RF2_ATTN_CASE(64, 128)
+  RF2_ATTN_CASE(256, 128)
+  RF2_ATTN_CASE(256, 64)
+#undef RF2_ATTN_CASE
+  return RF2_ERR_UNSUPPORTED;
 }
 
 int dispatch_attn(const rf2_plan* plan, const void* qp, const void* kp, const void* vp, const int32_t* blk_idx,
                   const int32_t* blk_cnt, void* out, float* lse, bool scatter, void* stream) {
   if (!plan || !qp || !kp || !vp || !blk_idx || !blk_cnt || !out) return RF2_ERR_INVALID_ARG;
   if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
-  const rf2_config& c = plan->cfg;
   hipStream_t st = (hipStream_t)stream;
-  if (c.head_dim == 128 && c.block == 128) return launch_attn<128, 128>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
-  if (c.head_dim == 64 && c.block == 64) return launch_attn<64, 64>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
-  if (c.head_dim == 128 && c.block == 64) return launch_attn<128, 64>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
-  if (c.head_dim == 64 && c.block == 128) return launch_attn<64, 128>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
+  if (plan->cfg.head_dim == 128) return dispatch_blocks<128>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
+  if (plan->cfg.head_dim == 64) return dispatch_blocks<64>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
   return RF2_ERR_UNSUPPORTED;
 }
 

@@ -1,7 +1,7 @@
 // Block-mask prediction: S_hat = qbar kbar^T (Sec. 3.2, eq. 7) in fp32 on the matrix cores,
 // then per-row top-n selection (eq. 8) with the first-frame sink (Sec. 3.4), fused in one
-// kernel.  A workgroup owns 16 rows of one head: its 4 wavefronts first fill a 16 x Tb
-// score strip in LDS, then each wavefront selects 4 of the rows with a bitwise threshold
+// kernel.  A workgroup owns 16 rows (Q blocks) of one head: its 4 wavefronts first fill a 16 x Tk
+// score strip in LDS (Tk = number of K blocks; the mask is Tq x Tk, square unless b_q != b_k), then each wavefront selects 4 of the rows with a bitwise threshold
 // search over order-preserving integer keys and emits the ascending block list.
 // The cumulative-mass variant (RF2_SELECT_CDF) runs the same search on probability mass
 // instead of counts: the threshold is the largest key whose upper set carries >= tau of the
@@ -37,13 +37,15 @@ template <int D, int EMAX, bool CDF>
 __global__ void __launch_bounds__(256) predict_mask_kernel(
     const float* __restrict__ qbar, const float* __restrict__ kbar, int32_t* __restrict__ blk_idx,
     int32_t* __restrict__ blk_cnt, uint8_t* __restrict__ mask_dense, float* __restrict__ scores,
-    int Tb, int LD, int sink_begin, int sink_end, int k_row, int k_sel, float tau, float scale_log2) {
+    int Tq, int Tb, int LD, int row_sink_begin, int row_sink_end, int sink_begin, int sink_end, int k_row, int k_sel,
+    float tau, float scale_log2) {
+  // Tb, sink_begin, sink_end describe the COLUMNS (K blocks) from here on; rows use Tq and row_sink_*.
   extern __shared__ __attribute__((aligned(16))) float sc[];   // [16][LD]
   const int bh = blockIdx.y;
   const int i0 = blockIdx.x * 16;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 15, lk = lane >> 4;
-  const float* __restrict__ qb = qbar + (size_t)bh * Tb * D;
+  const float* __restrict__ qb = qbar + (size_t)bh * Tq * D;
   const float* __restrict__ kb = kbar + (size_t)bh * Tb * D;
 
   // ---- scores: 16 x 16 tiles with v_mfma_f32_16x16x4_f32 -------------------------------
@@ -52,7 +54,7 @@ __global__ void __launch_bounds__(256) predict_mask_kernel(
   // 16*kk + 4*lk + e in both operands (a dot product does not care about summation order).
   f32x4 a[D / 16];
   {
-    const int row = min(i0 + lr, Tb - 1);
+    const int row = min(i0 + lr, Tq - 1);
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk) a[kk] = *reinterpret_cast<const f32x4*>(qb + (size_t)row * D + 16 * kk + 4 * lk);
   }
@@ -73,9 +75,9 @@ __global__ void __launch_bounds__(256) predict_mask_kernel(
   __syncthreads();
 
   if (scores != nullptr) {
-    for (int r = 0; r < 16 && i0 + r < Tb; ++r)
+    for (int r = 0; r < 16 && i0 + r < Tq; ++r)
       for (int j = threadIdx.x; j < Tb; j += 256)
-        scores[((size_t)bh * Tb + i0 + r) * Tb + j] = sc[r * LD + j];
+        scores[((size_t)bh * Tq + i0 + r) * Tb + j] = sc[r * LD + j];
   }
 
   // ---- selection: wavefront `wave` handles rows wave, wave+4, wave+8, wave+12 ------------
@@ -83,11 +85,11 @@ __global__ void __launch_bounds__(256) predict_mask_kernel(
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
   for (int r = wave; r < 16; r += 4) {
     const int i = i0 + r;
-    if (i >= Tb) break;
-    int32_t* __restrict__ out = blk_idx + ((size_t)bh * Tb + i) * k_row;
-    uint8_t* __restrict__ mrow = mask_dense ? mask_dense + ((size_t)bh * Tb + i) * Tb : nullptr;
-    if (i >= sink_begin && i < sink_end) {          // sink row: keeps every column
-      if (lane == 0) blk_cnt[(size_t)bh * Tb + i] = Tb;
+    if (i >= Tq) break;
+    int32_t* __restrict__ out = blk_idx + ((size_t)bh * Tq + i) * k_row;
+    uint8_t* __restrict__ mrow = mask_dense ? mask_dense + ((size_t)bh * Tq + i) * Tb : nullptr;
+    if (i >= row_sink_begin && i < row_sink_end) {  // sink row: keeps every column
+      if (lane == 0) blk_cnt[(size_t)bh * Tq + i] = Tb;
       for (int j = lane; j < k_row; j += 64) out[j] = j;
       if (mrow) for (int j = lane; j < Tb; j += 64) mrow[j] = 1;
       continue;
@@ -169,7 +171,7 @@ __global__ void __launch_bounds__(256) predict_mask_kernel(
         out_run += popc64(sel_m);
       }
     }
-    if (lane == 0) blk_cnt[(size_t)bh * Tb + i] = out_run;   // top-n: == k_row by construction
+    if (lane == 0) blk_cnt[(size_t)bh * Tq + i] = out_run;   // top-n: == k_row by construction
   }
 }
 
@@ -183,11 +185,11 @@ extern "C" int rf2_predict_mask(const rf2_plan* plan, const float* qbar, const f
   if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
   const rf2_config& c = plan->cfg;
   const rf2_info& in = plan->info;
-  const int Tb = in.n_blocks;
+  const int Tq = in.n_blocks, Tb = in.n_blocks_k;    // rows and columns of the block mask
   const int E = (Tb + 63) / 64;
   const int LD = E * 64 + 4;                        // +4: the 4 row groups of a tile store hit distinct banks
   const size_t lds = (size_t)16 * LD * sizeof(float);
-  const dim3 grid((Tb + 15) / 16, c.batch * c.heads, 1);
+  const dim3 grid((Tq + 15) / 16, c.batch * c.heads, 1);
   hipStream_t st = (hipStream_t)stream;
   const bool cdf = (c.select_mode == RF2_SELECT_CDF);
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)c.head_dim));
@@ -196,8 +198,9 @@ extern "C" int rf2_predict_mask(const rf2_plan* plan, const float* qbar, const f
     auto kern = cdf ? predict_mask_kernel<DD, EE, true> : predict_mask_kernel<DD, EE, false>;                   \
     if (lds > 48 * 1024)                                                                                        \
       RF2_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));    \
-    kern<<<grid, 256, lds, st>>>(qbar, kbar, blk_idx, blk_cnt, mask_dense, scores, Tb, LD, in.sink_block_begin, \
-                                 in.sink_block_end, in.k_row, in.k_sel, c.cdf_threshold, scale_log2);            \
+    kern<<<grid, 256, lds, st>>>(qbar, kbar, blk_idx, blk_cnt, mask_dense, scores, Tq, Tb, LD,                 \
+                                 in.sink_block_begin, in.sink_block_end, in.sink_block_begin_k,               \
+                                 in.sink_block_end_k, in.k_row, in.k_sel, c.cdf_threshold, scale_log2);       \
     RF2_LAUNCH_CHECK();                                                                                         \
     return RF2_OK;                                                                                              \
   }

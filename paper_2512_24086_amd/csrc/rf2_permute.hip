@@ -11,39 +11,37 @@ typedef unsigned short u16;
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// One workgroup gathers one block of BLK permuted rows of Q (blockIdx.z = 0) or K (1),
+// One workgroup gathers one block of BLK permuted rows of Q (IS_K = false) or K (true),
 // writes them in permuted order and reduces their column sums to the block mean.
 // Q rows stay row-major; a K block is written as BLK/64 operand parts [D/8][64][8]: with
 // KH = BLK/2, the 16-byte chunk c of block row r lands in part (r % KH) / 32 at chunk slot
 // c*64 + (r / KH)*32 + r % 32 -- the order in which the attention kernel's matrix-core
 // operand reads walk it (a part holds one 32-key tile of each key half).
-template <int D, int BLK>
+template <int D, int BLK, bool IS_K>
 __global__ void __launch_bounds__(256) permute_pool_kernel(
-    const uint4* __restrict__ q, const uint4* __restrict__ k, uint4* __restrict__ qp, uint4* __restrict__ kp,
-    float* __restrict__ qbar, float* __restrict__ kbar, const int32_t* __restrict__ perm,
+    const uint4* __restrict__ x, uint4* __restrict__ xp, float* __restrict__ mean, const int32_t* __restrict__ perm,
     int N, int n_blocks, int last_valid, int heads, rf2_strides st) {
   constexpr int CH = D / 8;          // 16-byte chunks per row
   constexpr int RG = 256 / CH;       // rows moved per pass
   const int blk = blockIdx.x;
   const int bh = blockIdx.y;
-  const uint4* __restrict__ src = (blockIdx.z == 0 ? q : k) + ((bh / heads) * st.batch + (bh % heads) * st.head) * CH;
-  uint4* __restrict__ dst = (blockIdx.z == 0 ? qp : kp) + ((size_t)bh * n_blocks + blk) * BLK * CH;
-  float* __restrict__ mean = blockIdx.z == 0 ? qbar : kbar;
+  const uint4* __restrict__ src = x + ((bh / heads) * st.batch + (bh % heads) * st.head) * CH;
+  uint4* __restrict__ dst = xp + ((size_t)bh * n_blocks + blk) * BLK * CH;
   const int c = threadIdx.x % CH, rg = threadIdx.x / CH;
 
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
   for (int r = rg; r < BLK; r += RG) {
     const int n = perm[blk * BLK + r];
-    uint4 x = make_uint4(0u, 0u, 0u, 0u);
-    if (n >= 0) x = src[(size_t)n * st.token * CH + c];
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (n >= 0) v = src[(size_t)n * st.token * CH + c];
     constexpr int KH = BLK / 2;
     const int kslot = ((r % KH) / 32 * CH + c) * 64 + (r / KH) * 32 + r % 32;
-    dst[blockIdx.z == 0 ? r * CH + c : kslot] = x;
-    acc[0] += bf16_lo(x.x); acc[1] += bf16_hi(x.x);
-    acc[2] += bf16_lo(x.y); acc[3] += bf16_hi(x.y);
-    acc[4] += bf16_lo(x.z); acc[5] += bf16_hi(x.z);
-    acc[6] += bf16_lo(x.w); acc[7] += bf16_hi(x.w);
+    dst[IS_K ? kslot : r * CH + c] = v;
+    acc[0] += bf16_lo(v.x); acc[1] += bf16_hi(v.x);
+    acc[2] += bf16_lo(v.y); acc[3] += bf16_hi(v.y);
+    acc[4] += bf16_lo(v.z); acc[5] += bf16_hi(v.z);
+    acc[6] += bf16_lo(v.w); acc[7] += bf16_hi(v.w);
   }
   if (mean == nullptr) return;
   __shared__ float part[RG][D + 1];
@@ -126,32 +124,58 @@ __global__ void __launch_bounds__(256) unpermute_kernel(
 
 }  // namespace
 
+namespace {
+
+template <int D, int BQ>
+void launch_permute_q(const rf2_plan* plan, const void* q, void* qp, float* qbar, hipStream_t st) {
+  const rf2_info& in = plan->info;
+  const dim3 grid(in.n_blocks, plan->cfg.batch * plan->cfg.heads, 1);
+  permute_pool_kernel<D, BQ, false><<<grid, 256, 0, st>>>((const uint4*)q, (uint4*)qp, qbar, plan->d_perm, (int)in.N,
+                                                           in.n_blocks, in.last_block_valid, plan->cfg.heads,
+                                                           rf2_qkv_strides(plan));
+}
+
+template <int D, int BK>
+void launch_permute_kv(const rf2_plan* plan, const void* k, const void* v, void* kp, void* vp, float* kbar,
+                       hipStream_t st) {
+  const rf2_info& in = plan->info;
+  const dim3 grid(in.n_blocks_k, plan->cfg.batch * plan->cfg.heads, 1);
+  permute_pool_kernel<D, BK, true><<<grid, 256, 0, st>>>((const uint4*)k, (uint4*)kp, kbar, plan->d_perm, (int)in.N,
+                                                          in.n_blocks_k, in.last_block_valid_k, plan->cfg.heads,
+                                                          rf2_qkv_strides(plan));
+  permute_vtile_kernel<D, BK><<<grid, 256, 0, st>>>((const uint4*)v, (uint4*)vp, plan->d_perm, (int)in.N,
+                                                     in.n_blocks_k, plan->cfg.heads, rf2_qkv_strides(plan));
+}
+
+template <int D>
+int permute_for_dim(const rf2_plan* plan, const void* q, const void* k, const void* v, void* qp, void* kp, void* vp,
+                    float* qbar, float* kbar, hipStream_t st) {
+  switch (plan->cfg.block) {
+    case 64: launch_permute_q<D, 64>(plan, q, qp, qbar, st); break;
+    case 128: launch_permute_q<D, 128>(plan, q, qp, qbar, st); break;
+    case 256: launch_permute_q<D, 256>(plan, q, qp, qbar, st); break;
+    default: return RF2_ERR_UNSUPPORTED;
+  }
+  RF2_LAUNCH_CHECK();
+  switch (plan->info.block_k) {
+    case 64: launch_permute_kv<D, 64>(plan, k, v, kp, vp, kbar, st); break;
+    case 128: launch_permute_kv<D, 128>(plan, k, v, kp, vp, kbar, st); break;
+    default: return RF2_ERR_UNSUPPORTED;
+  }
+  RF2_LAUNCH_CHECK();
+  return RF2_OK;
+}
+
+}  // namespace
+
 extern "C" int rf2_permute(const rf2_plan* plan, const void* q, const void* k, const void* v, void* qp, void* kp,
                            void* vp, float* qbar, float* kbar, void* stream) {
   if (!plan || !q || !k || !v || !qp || !kp || !vp) return RF2_ERR_INVALID_ARG;
   if ((qbar == nullptr) != (kbar == nullptr)) return RF2_ERR_INVALID_ARG;
   if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
-  const rf2_config& c = plan->cfg;
-  const rf2_info& in = plan->info;
   hipStream_t st = (hipStream_t)stream;
-  const dim3 grid_qk(in.n_blocks, c.batch * c.heads, 2), grid_v(in.n_blocks, c.batch * c.heads, 1);
-  const rf2_strides strides = rf2_qkv_strides(plan);
-#define RF2_PERMUTE_CASE(DD, BB)                                                                              \
-  if (c.head_dim == DD && c.block == BB) {                                                                    \
-    permute_pool_kernel<DD, BB><<<grid_qk, 256, 0, st>>>((const uint4*)q, (const uint4*)k, (uint4*)qp,        \
-                                                          (uint4*)kp, qbar, kbar, plan->d_perm, (int)in.N,     \
-                                                          in.n_blocks, in.last_block_valid, c.heads, strides);  \
-    RF2_LAUNCH_CHECK();                                                                                       \
-    permute_vtile_kernel<DD, BB><<<grid_v, 256, 0, st>>>((const uint4*)v, (uint4*)vp, plan->d_perm, (int)in.N, \
-                                                          in.n_blocks, c.heads, strides);                      \
-    RF2_LAUNCH_CHECK();                                                                                       \
-    return RF2_OK;                                                                                            \
-  }
-  RF2_PERMUTE_CASE(128, 128)
-  RF2_PERMUTE_CASE(64, 64)
-  RF2_PERMUTE_CASE(128, 64)
-  RF2_PERMUTE_CASE(64, 128)
-#undef RF2_PERMUTE_CASE
+  if (plan->cfg.head_dim == 128) return permute_for_dim<128>(plan, q, k, v, qp, kp, vp, qbar, kbar, st);
+  if (plan->cfg.head_dim == 64) return permute_for_dim<64>(plan, q, k, v, qp, kp, vp, qbar, kbar, st);
   return RF2_ERR_UNSUPPORTED;
 }
 

@@ -18,8 +18,17 @@ struct Window {
 
 // Default window: volume equals the block so that an interior window is exactly one block.
 Window default_window(int block, bool video) {
+  if (block == 256) return video ? Window{4, 8, 8} : Window{1, 16, 16};
   if (block == 128) return video ? Window{2, 8, 8} : Window{1, 8, 16};
   return video ? Window{4, 4, 4} : Window{1, 8, 8};
+}
+
+// [begin, end) of the blocks of b tokens that hold at least one always-dense token (Sec. 3.4).
+void dense_block_range(int64_t N, int64_t n_sink, int64_t n_text, bool tail, int b, int32_t* begin, int32_t* end) {
+  const int32_t Tb = (int32_t)((N + b - 1) / b);
+  if (n_sink + n_text == 0) { *begin = *end = 0; }
+  else if (tail) { *begin = (int32_t)((N - n_sink - n_text) / b); *end = Tb; }
+  else { *begin = 0; *end = (int32_t)((n_sink + b - 1) / b); }
 }
 
 // Position of token (tp, h, w) inside a group of Tn frames ordered window by window
@@ -81,7 +90,9 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
   const bool win_default = (c.wt == 0 && c.wh == 0 && c.ww == 0);
   if (!win_default && (c.wt < 1 || c.wh < 1 || c.ww < 1)) return RF2_ERR_INVALID_ARG;
   if (c.head_dim != 64 && c.head_dim != 128) return RF2_ERR_UNSUPPORTED;
-  if (c.block != 64 && c.block != 128) return RF2_ERR_UNSUPPORTED;
+  if (c.block != 64 && c.block != 128 && c.block != 256) return RF2_ERR_UNSUPPORTED;
+  if (c.block_k != 0 && c.block_k != 64 && c.block_k != 128) return RF2_ERR_UNSUPPORTED;
+  if (c.block_k == 0 && c.block == 256) return RF2_ERR_UNSUPPORTED;   // K/V blocks have 64 or 128 rows
   const int64_t n_video = (int64_t)c.T * c.H * c.W;
   const int64_t N = n_video + c.text_tokens;
   if (N > (int64_t)1 << 24) return RF2_ERR_UNSUPPORTED;  // 16 Mi tokens: keeps every index in int32
@@ -94,49 +105,48 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
   const Window win = win_default ? default_window(c.block, c.T > 1) : Window{c.wt, c.wh, c.ww};
 
   rf2_info& in = p->info;
-  const int b = c.block;
+  const int b = c.block, bk = c.block_k ? c.block_k : c.block;
   in.N = N;
   in.n_blocks = (int32_t)((N + b - 1) / b);
   in.N_pad = (int64_t)in.n_blocks * b;
   in.last_block_valid = (int32_t)(N - (int64_t)(in.n_blocks - 1) * b);
+  in.block_k = bk;
+  in.n_blocks_k = (int32_t)((N + bk - 1) / bk);
+  in.N_pad_k = (int64_t)in.n_blocks_k * bk;
+  in.last_block_valid_k = (int32_t)(N - (int64_t)(in.n_blocks_k - 1) * bk);
   in.wt = win.wt; in.wh = win.wh; in.ww = win.ww;
-  const int Tb = in.n_blocks;
-  if (Tb > 2048) { delete p; return RF2_ERR_UNSUPPORTED; }  // one row of block scores must fit the selection kernel's LDS
+  const int Tb = in.n_blocks, Tk = in.n_blocks_k;       // rows and columns of the block mask
+  if (Tb > 2048 || Tk > 2048) { delete p; return RF2_ERR_UNSUPPORTED; }  // one row of block scores must fit the selection kernel's LDS
 
   // Always-dense blocks: every block that holds at least one sink-frame or text token (Sec. 3.4).
   const int64_t frame = (int64_t)c.H * c.W;
   const int64_t n_sink = (int64_t)c.sink_frames * frame;
-  if (n_sink + c.text_tokens == 0) {
-    in.sink_block_begin = in.sink_block_end = 0;
-  } else if (c.sink_at_end || n_sink == 0) {
-    in.sink_block_begin = (int32_t)((N - n_sink - c.text_tokens) / b);
-    in.sink_block_end = Tb;
-  } else {
-    in.sink_block_begin = 0;
-    in.sink_block_end = (int32_t)((n_sink + b - 1) / b);
-  }
-  const int nS = in.sink_block_end - in.sink_block_begin;
+  const bool tail = c.sink_at_end || n_sink == 0;
+  dense_block_range(N, n_sink, c.text_tokens, tail, b, &in.sink_block_begin, &in.sink_block_end);
+  dense_block_range(N, n_sink, c.text_tokens, tail, bk, &in.sink_block_begin_k, &in.sink_block_end_k);
+  const int nS = in.sink_block_end - in.sink_block_begin;          // sink rows
+  const int nSk = in.sink_block_end_k - in.sink_block_begin_k;     // sink columns
 
-  // Blocks kept per non-sink row.  The sparsity is a float; the arithmetic is double.
+  // K blocks kept per non-sink row.  The sparsity is a float; the arithmetic is double.
   const double keep = 1.0 - (double)c.sparsity;
   int k_row;
   if (nS >= Tb) {
-    k_row = Tb;
+    k_row = Tk;
   } else {
     if (c.budget_mode == RF2_BUDGET_GLOBAL)
-      k_row = (int)std::floor((keep * Tb * Tb - (double)nS * Tb) / (double)(Tb - nS));
+      k_row = (int)std::floor((keep * Tb * Tk - (double)nS * Tk) / (double)(Tb - nS));
     else if (c.budget_mode == RF2_BUDGET_ROW_INCL_SINK)
-      k_row = (int)std::ceil(keep * Tb);
+      k_row = (int)std::ceil(keep * Tk);
     else
-      k_row = (int)std::ceil(keep * Tb) + nS;
-    k_row = std::min(std::max(std::max(k_row, nS), 1), Tb);
+      k_row = (int)std::ceil(keep * Tk) + nSk;
+    k_row = std::min(std::max(std::max(k_row, nSk), 1), Tk);
   }
   in.k_row = k_row;
-  in.k_sel = nS >= Tb ? 0 : k_row - nS;
-  in.kept_pairs_per_head = (int64_t)(Tb - nS) * k_row + (int64_t)nS * Tb;
-  in.achieved_sparsity = 1.0 - (double)in.kept_pairs_per_head / ((double)Tb * Tb);
+  in.k_sel = nS >= Tb ? 0 : k_row - nSk;
+  in.kept_pairs_per_head = (int64_t)(Tb - nS) * k_row + (int64_t)nS * Tk;
+  in.achieved_sparsity = 1.0 - (double)in.kept_pairs_per_head / ((double)Tb * Tk);
   if (c.select_mode == RF2_SELECT_CDF) {   // row lengths depend on the data: k_row is the list capacity
-    in.k_row = Tb;
+    in.k_row = Tk;
     in.k_sel = 0;
     in.kept_pairs_per_head = -1;
     in.achieved_sparsity = -1.0;
@@ -189,7 +199,7 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
     for (size_t r = 0; r < plain_xcd[x].size(); ++r) order[x * (spx + ppx) + spx + r] = plain_xcd[x][r];
   }
 
-  std::vector<int32_t> perm_pad((size_t)in.N_pad, -1);
+  std::vector<int32_t> perm_pad((size_t)std::max(in.N_pad, in.N_pad_k), -1);
   std::memcpy(perm_pad.data(), p->perm.data(), (size_t)N * sizeof(int32_t));
 
   // Without a HIP device the plan stays host-only: info and tables work, compute calls fail.

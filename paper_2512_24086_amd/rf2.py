@@ -24,7 +24,7 @@ class rf2_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("batch", "heads", "head_dim", "T", "H", "W", "wt", "wh", "ww",
                                          "block", "sink_frames", "sink_at_end")] + \
                [("sparsity", C.c_float), ("budget_mode", C.c_int32), ("qkv_layout", C.c_int32), ("text_tokens", C.c_int32),
-                ("select_mode", C.c_int32), ("cdf_threshold", C.c_float)]
+                ("select_mode", C.c_int32), ("cdf_threshold", C.c_float), ("block_k", C.c_int32)]
 
 
 class rf2_info(C.Structure):
@@ -32,7 +32,9 @@ class rf2_info(C.Structure):
                 ("sink_block_begin", C.c_int32), ("sink_block_end", C.c_int32), ("k_row", C.c_int32),
                 ("k_sel", C.c_int32), ("wt", C.c_int32), ("wh", C.c_int32), ("ww", C.c_int32),
                 ("kept_pairs_per_head", C.c_int64), ("achieved_sparsity", C.c_double),
-                ("workspace_bytes", C.c_int64)]
+                ("workspace_bytes", C.c_int64), ("block_k", C.c_int32), ("n_blocks_k", C.c_int32),
+                ("last_block_valid_k", C.c_int32), ("sink_block_begin_k", C.c_int32), ("sink_block_end_k", C.c_int32),
+                ("N_pad_k", C.c_int64)]
 
 
 # symbol -> (restype, argtypes); also the list of exports the tests check
@@ -104,11 +106,11 @@ class Plan:
 
     def __init__(self, *, batch, heads, head_dim, T, H, W, block, sparsity, sink_frames=0, sink_at_end=1,
                  window=(0, 0, 0), budget_mode=RF2_BUDGET_GLOBAL, qkv_layout=RF2_LAYOUT_BHND, text_tokens=0,
-                 cdf_threshold=None):
+                 cdf_threshold=None, block_k=0):
         self.cfg = rf2_config(batch, heads, head_dim, T, H, W, window[0], window[1], window[2], block,
                               sink_frames, int(sink_at_end), float(sparsity), budget_mode, qkv_layout, text_tokens,
                               RF2_SELECT_TOPN if cdf_threshold is None else RF2_SELECT_CDF,
-                              0.0 if cdf_threshold is None else float(cdf_threshold))
+                              0.0 if cdf_threshold is None else float(cdf_threshold), block_k)
         self._h = C.c_void_p(0)
         _check(lib().rf2_plan_create(C.byref(self.cfg), C.byref(self._h)), "rf2_plan_create")
         self.info = rf2_info()
@@ -140,19 +142,19 @@ class Plan:
         bf = dict(dtype=torch.bfloat16, device=device)
         buf = dict(
             qp=torch.empty(*bh, i.N_pad, c.head_dim, **bf),
-            kp=torch.empty(*bh, i.n_blocks, c.block // 64, c.head_dim // 8, 64, 8, **bf),
-            vp=torch.empty(*bh, i.n_blocks, c.block // 64, 8, c.head_dim, 8, **bf),
+            kp=torch.empty(*bh, i.n_blocks_k, i.block_k // 64, c.head_dim // 8, 64, 8, **bf),
+            vp=torch.empty(*bh, i.n_blocks_k, i.block_k // 64, 8, c.head_dim, 8, **bf),
             qbar=torch.empty(*bh, i.n_blocks, c.head_dim, dtype=torch.float32, device=device),
-            kbar=torch.empty(*bh, i.n_blocks, c.head_dim, dtype=torch.float32, device=device),
+            kbar=torch.empty(*bh, i.n_blocks_k, c.head_dim, dtype=torch.float32, device=device),
             blk_idx=torch.empty(*bh, i.n_blocks, i.k_row, dtype=torch.int32, device=device),
             blk_cnt=torch.empty(*bh, i.n_blocks, dtype=torch.int32, device=device),
             op=torch.empty(*bh, i.N_pad, c.head_dim, **bf),
             o=(torch.empty(c.batch, i.N, c.heads, c.head_dim, **bf) if c.qkv_layout == RF2_LAYOUT_BNHD
                else torch.empty(*bh, i.N, c.head_dim, **bf)))
         if dense_mask:
-            buf["mask_dense"] = torch.empty(*bh, i.n_blocks, i.n_blocks, dtype=torch.uint8, device=device)
+            buf["mask_dense"] = torch.empty(*bh, i.n_blocks, i.n_blocks_k, dtype=torch.uint8, device=device)
         if scores:
-            buf["scores"] = torch.empty(*bh, i.n_blocks, i.n_blocks, dtype=torch.float32, device=device)
+            buf["scores"] = torch.empty(*bh, i.n_blocks, i.n_blocks_k, dtype=torch.float32, device=device)
         if lse:
             buf["lse"] = torch.empty(*bh, i.N_pad, dtype=torch.float32, device=device)
         return buf

@@ -46,15 +46,16 @@ def vp_to_rows(vp: np.ndarray) -> np.ndarray:
 
 
 def lists_to_device(M_heads, k_row, Tb, device):
-    """Oracle masks [heads][Tb,Tb] -> (blk_idx [1,heads,Tb,k_row], blk_cnt [1,heads,Tb]) tensors."""
+    """Oracle masks [heads][Tq,Tk] -> (blk_idx [1,heads,Tq,k_row], blk_cnt [1,heads,Tq]) tensors."""
     Hh = len(M_heads)
+    Tb, Tk = M_heads[0].shape
     idx = np.zeros((1, Hh, Tb, k_row), dtype=np.int32)
     cnt = np.zeros((1, Hh, Tb), dtype=np.int32)
     for h, M in enumerate(M_heads):
         for i in range(Tb):
             cols = np.flatnonzero(M[i]).astype(np.int32)
-            if cols.size == Tb:
-                cnt[0, h, i] = Tb
+            if cols.size == Tk:
+                cnt[0, h, i] = Tk
                 idx[0, h, i, :] = np.arange(k_row)
             else:
                 assert cols.size <= k_row
@@ -63,17 +64,18 @@ def lists_to_device(M_heads, k_row, Tb, device):
     return torch.from_numpy(idx).to(device), torch.from_numpy(cnt).to(device)
 
 
-def gpu_lists_to_mask(blk_idx, blk_cnt, Tb):
-    """Device lists of one head -> boolean [Tb,Tb]; checks the list format on the way."""
+def gpu_lists_to_mask(blk_idx, blk_cnt, Tb, Tk=None):
+    """Device lists of one head -> boolean [Tb,Tk] (Tk = Tb unless given); checks the list format on the way."""
     idx, cnt = blk_idx.cpu().numpy(), blk_cnt.cpu().numpy()
-    M = np.zeros((Tb, Tb), dtype=bool)
+    Tk = Tb if Tk is None else Tk
+    M = np.zeros((Tb, Tk), dtype=bool)
     for i in range(Tb):
-        if cnt[i] == Tb:
+        if cnt[i] == Tk:
             M[i] = True
         else:
             cols = idx[i, :cnt[i]]
             assert (np.diff(cols) > 0).all(), "block list must be strictly ascending"
-            assert cols.min() >= 0 and cols.max() < Tb
+            assert cols.min() >= 0 and cols.max() < Tk
             M[i, cols] = True
     return M
 
@@ -92,4 +94,5 @@ def oracle_layer(wl, q, k, v, head, plan, q_blocks=None, sparsity=None):
     return orc.layer(Q, K, V, T=c.T, H=c.H, W=c.W, block=c.block, sparsity=c.sparsity, sink_frames=c.sink_frames,
                      sink_at_end=bool(c.sink_at_end), window=(plan.info.wt, plan.info.wh, plan.info.ww),
                      budget_mode=c.budget_mode, q_blocks=q_blocks, text_tokens=c.text_tokens,
-                     cdf_threshold=float(c.cdf_threshold) if c.select_mode == rf2.RF2_SELECT_CDF else None)
+                     cdf_threshold=float(c.cdf_threshold) if c.select_mode == rf2.RF2_SELECT_CDF else None,
+                     block_k=plan.info.block_k)

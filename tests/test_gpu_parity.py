@@ -28,6 +28,12 @@ SMALL = {
     "tiny_cdf": (inputs.WORKLOADS["tiny"], dict(cdf_threshold=0.7)),
     "ragged_cdf_d128": (inputs.Workload("raggedcdf", 15, 1, 3, 128, 5, 10, 13, 128, 0.5, 1, 0.3, text_tokens=9),
                         dict(cdf_threshold=0.9)),
+    # different block sizes for Q and K (rectangular block mask)
+    "q128_k64": (inputs.Workload("q128k64", 16, 1, 2, 128, 5, 10, 13, 128, 0.5, 1, 0.3), dict(block_k=64)),
+    "q64_k128_d64": (inputs.Workload("q64k128", 17, 1, 2, 64, 6, 16, 16, 64, 0.5, 1, 0.3), dict(block_k=128)),
+    "q256_k128": (inputs.Workload("q256k128", 18, 1, 2, 128, 7, 12, 16, 256, 0.6, 1, 0.3, text_tokens=30),
+                  dict(block_k=128)),
+    "q256_k64_d64": (inputs.Workload("q256k64", 19, 1, 2, 64, 5, 12, 16, 256, 0.5, 1, 0.3), dict(block_k=64)),
 }
 
 
@@ -69,25 +75,27 @@ def test_block_means(case):
     for h in range(wl.heads):
         for name in ("qbar", "kbar"):
             got = buf[name][0, h].double().cpu().numpy()
-            # fp32 sum of <=128 bf16 values of magnitude ~1, then one division
-            assert np.abs(got - ref[h][name]).max() < 2e-6, name
+            # fp32 sum of <=128 (256 for the largest Q block) bf16 values of magnitude ~1, then one division
+            assert np.abs(got - ref[h][name]).max() < (4e-6 if plan.cfg.block == 256 else 2e-6), name
 
 
 def test_scores_and_block_mask(case):
     wl, plan, _, _, buf, ref = case
     i = plan.info
-    Tb = i.n_blocks
+    Tb, Tk = i.n_blocks, i.n_blocks_k             # rows (Q blocks) and columns (K blocks) of the mask
     near_ties = 0
     for h in range(wl.heads):
         S = buf["scores"][0, h].double().cpu().numpy()
         assert np.abs(S - ref[h]["S_hat"]).max() < 1e-4          # fp32 dot products of length d, |S| ~ 10
-        M = hp.gpu_lists_to_mask(buf["blk_idx"][0, h], buf["blk_cnt"][0, h], Tb)
+        M = hp.gpu_lists_to_mask(buf["blk_idx"][0, h], buf["blk_cnt"][0, h], Tb, Tk)
         assert np.array_equal(M, buf["mask_dense"][0, h].cpu().numpy().astype(bool)), "list and dense mask disagree"
         cnt = buf["blk_cnt"][0, h].cpu().numpy()
         sink = np.zeros(Tb, dtype=bool)
         sink[i.sink_block_begin:i.sink_block_end] = True
+        sink_cols = np.zeros(Tk, dtype=bool)
+        sink_cols[i.sink_block_begin_k:i.sink_block_end_k] = True
         cdf = plan.cfg.select_mode == 1
-        assert (cnt[sink] == Tb).all() and M[:, sink].all() and M[sink].all()
+        assert (cnt[sink] == Tk).all() and M[:, sink_cols].all() and M[sink].all()
         clear = ref[h]["gap"] > (hp.CDF_TIE if cdf else hp.TIE_GAP)
         near_ties += int((~clear & ~sink).sum())
         assert np.array_equal(M[clear], ref[h]["M"][clear]), "mask differs on a row with a clear boundary"
@@ -96,7 +104,7 @@ def test_scores_and_block_mask(case):
             if (~sink).sum() >= 16:
                 assert len(set(cnt[~sink])) > 1, "cumulative-mass rows should differ in length on these inputs"
         else:
-            assert (cnt[~sink] == (i.k_row if i.k_row < Tb else Tb)).all()
+            assert (cnt[~sink] == i.k_row).all()
             assert (M.sum(1) == ref[h]["M"].sum(1)).all()
     print(f"[mask] near-tie rows exempted: {near_ties}")
 
@@ -125,11 +133,12 @@ def test_whole_layer_and_unpermute(case):
         op_bits = inputs.bf16_bits(buf["op"][0, h])[:i.N]
         o_bits = inputs.bf16_bits(buf["o"][0, h])
         assert np.array_equal(o_bits[ref[h]["perm"]], op_bits), "unpermute must be a bit-exact scatter"
-        M = hp.gpu_lists_to_mask(buf["blk_idx"][0, h], buf["blk_cnt"][0, h], i.n_blocks)
+        M = hp.gpu_lists_to_mask(buf["blk_idx"][0, h], buf["blk_cnt"][0, h], i.n_blocks, i.n_blocks_k)
         if np.array_equal(M, ref[h]["M"]):
             want = ref[h]["O"]
         else:                                  # near-tie rows chose differently: oracle attention on the GPU's mask
-            Op = orc.block_sparse_attention(ref[h]["Qp"], ref[h]["Kp"], ref[h]["Vp"], M, plan.cfg.block)
+            Op = orc.block_sparse_attention(ref[h]["Qp"], ref[h]["Kp"], ref[h]["Vp"], M, plan.cfg.block,
+                                            bk=plan.info.block_k)
             want = orc.unpermute(Op, ref[h]["perm"])
         err = np.abs(hp.f64(buf["o"][0, h]) - want)
         assert err.max() <= hp.ATTN_MAX_ABS and err.mean() <= hp.ATTN_MEAN_ABS, (err.max(), err.mean())
@@ -257,10 +266,10 @@ def test_large_logits_take_the_reference_reset_path(scale):
     assert torch.isfinite(o.float()).all()
     for h in range(wl.heads):
         ref = hp.oracle_layer(wl, q, k, v, h, plan)
-        M = hp.gpu_lists_to_mask(buf["blk_idx"][0, h], buf["blk_cnt"][0, h], plan.info.n_blocks)
+        M = hp.gpu_lists_to_mask(buf["blk_idx"][0, h], buf["blk_cnt"][0, h], plan.info.n_blocks, plan.info.n_blocks_k)
         want = ref["O"]
         if not np.array_equal(M, ref["M"]):
-            Op = orc.block_sparse_attention(ref["Qp"], ref["Kp"], ref["Vp"], M, plan.cfg.block)
+            Op = orc.block_sparse_attention(ref["Qp"], ref["Kp"], ref["Vp"], M, plan.cfg.block, bk=plan.info.block_k)
             want = orc.unpermute(Op, ref["perm"])
         err = np.abs(hp.f64(o[0, h]) - want)
         assert err.max() <= hp.ATTN_MAX_ABS and err.mean() <= hp.ATTN_MEAN_ABS, (scale, err.max(), err.mean())

@@ -49,7 +49,8 @@ def test_invalid_configs_are_rejected(bad):
 
 
 @pytest.mark.parametrize("bad", [dict(head_dim=96), dict(block=32), dict(T=4096, H=256, W=256),
-                                 dict(text_tokens=5, sink_at_end=0)])   # dense tokens in two separate runs
+                                 dict(text_tokens=5, sink_at_end=0),     # dense tokens in two separate runs
+                                 dict(block=256), dict(block_k=256), dict(block_k=32), dict(block=256, block_k=256)])
 def test_unsupported_configs_are_rejected(bad):
     with pytest.raises(rf2.Rf2Error) as e:
         make_plan(**bad)
@@ -135,4 +136,39 @@ def test_cdf_mode_reports_capacity_not_a_budget():
     p = make_plan(cdf_threshold=0.8)
     i = p.info
     assert (i.k_row, i.k_sel, i.kept_pairs_per_head, i.achieved_sparsity) == (i.n_blocks, 0, -1, -1.0)
+    p.close()
+
+
+@pytest.mark.parametrize("case", [
+    # T, H, W, b_q, b_k, sink_frames, text_tokens, sparsity
+    (21, 45, 80, 256, 128, 1, 0, 0.8), (21, 45, 80, 128, 64, 1, 0, 0.8), (6, 16, 16, 64, 128, 1, 0, 0.5),
+    (5, 7, 9, 256, 64, 1, 13, 0.6), (1, 40, 36, 128, 64, 0, 0, 0.5), (4, 9, 11, 64, 128, 1, 0, 0.7),
+])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_different_q_and_k_blocks_match_the_oracle(case, mode):
+    T, H, W, bq, bk, sf, text, s = case
+    p = make_plan(T=T, H=H, W=W, block=bq, block_k=bk, sink_frames=sf, text_tokens=text, sparsity=s,
+                  budget_mode=mode, head_dim=128)
+    i = p.info
+    N = T * H * W + text
+    Tq, Tk = orc.n_blocks(N, bq), orc.n_blocks(N, bk)
+    assert (i.N, i.n_blocks, i.n_blocks_k, i.block_k) == (N, Tq, Tk, bk)
+    assert (i.N_pad, i.N_pad_k) == (Tq * bq, Tk * bk)
+    assert (i.last_block_valid, i.last_block_valid_k) == (N - (Tq - 1) * bq, N - (Tk - 1) * bk)
+    rq = orc.sink_block_range(N, H * W, bq, sf, True, text)
+    rk = orc.sink_block_range(N, H * W, bk, sf, True, text)
+    assert (i.sink_block_begin, i.sink_block_end) == rq and (i.sink_block_begin_k, i.sink_block_end_k) == rk
+    k_row, k_sel = orc.budget(Tq, rq[1] - rq[0], s, mode, Tk, rk[1] - rk[0])
+    assert (i.k_row, i.k_sel) == (k_row, k_sel)
+    assert i.kept_pairs_per_head == orc.kept_pairs(Tq, rq[1] - rq[0], k_row, Tk)
+    assert abs(i.achieved_sparsity - (1 - i.kept_pairs_per_head / (Tq * Tk))) < 1e-12
+    assert (i.wt, i.wh, i.ww) == orc.default_window(bq, T > 1)
+    p.close()
+
+
+def test_equal_blocks_report_the_same_k_side():
+    p = make_plan()
+    i = p.info
+    assert (i.block_k, i.n_blocks_k, i.N_pad_k, i.last_block_valid_k) == (64, i.n_blocks, i.N_pad, i.last_block_valid)
+    assert (i.sink_block_begin_k, i.sink_block_end_k) == (i.sink_block_begin, i.sink_block_end)
     p.close()
