@@ -34,6 +34,12 @@ SMALL = {
     "q256_k128": (inputs.Workload("q256k128", 18, 1, 2, 128, 7, 12, 16, 256, 0.6, 1, 0.3, text_tokens=30),
                   dict(block_k=128)),
     "q256_k64_d64": (inputs.Workload("q256k64", 19, 1, 2, 64, 5, 12, 16, 256, 0.5, 1, 0.3), dict(block_k=64)),
+    # combinations: fewer tokens than one Q block; cumulative-mass rows over a rectangular mask with text tokens
+    "q256_single_block": (inputs.Workload("q256one", 20, 1, 1, 128, 1, 9, 11, 256, 0.5, 0, 0.3), dict(block_k=128)),
+    "q256_k128_cdf_text": (inputs.Workload("q256cdf", 21, 1, 2, 128, 6, 12, 16, 256, 0.5, 1, 0.3, text_tokens=70),
+                           dict(block_k=128, cdf_threshold=0.8)),
+    "q64_k128_sink_front": (inputs.Workload("q64front", 22, 1, 2, 128, 4, 9, 11, 64, 0.6, 1, 0.3),
+                            dict(block_k=128, sink_at_end=0)),
 }
 
 
