@@ -29,6 +29,9 @@ inline rf2_strides rf2_qkv_strides(const rf2_plan* p) {
   return {Hh * N, N, 1};
 }
 
+// Per-plan preparation of the mask kernel (dynamic LDS limit); defined in rf2_mask.hip.
+int rf2_mask_prepare(const rf2_plan* plan);
+
 // Remembers the text of a failed HIP call for rf2_strerror (per calling thread).
 int rf2_note_hip_error(hipError_t e);
 

@@ -175,7 +175,40 @@ __global__ void __launch_bounds__(256) predict_mask_kernel(
   }
 }
 
+// Shape of the launch for a plan, and the kernel instance that serves it.
+struct MaskLaunch {
+  const void* kernel;
+  int E, LD;
+  size_t lds;
+};
+
+template <int D>
+const void* mask_kernel_for(int E, bool cdf) {
+  if (E <= 16) return cdf ? (const void*)predict_mask_kernel<D, 16, true> : (const void*)predict_mask_kernel<D, 16, false>;
+  return cdf ? (const void*)predict_mask_kernel<D, 32, true> : (const void*)predict_mask_kernel<D, 32, false>;
+}
+
+MaskLaunch mask_launch(const rf2_plan* plan) {
+  MaskLaunch m;
+  m.E = (plan->info.n_blocks_k + 63) / 64;
+  m.LD = m.E * 64 + 4;                              // +4: the 4 row groups of a tile store hit distinct banks
+  m.lds = (size_t)16 * m.LD * sizeof(float);
+  const bool cdf = (plan->cfg.select_mode == RF2_SELECT_CDF);
+  m.kernel = plan->cfg.head_dim == 128 ? mask_kernel_for<128>(m.E, cdf) : mask_kernel_for<64>(m.E, cdf);
+  return m;
+}
+
 }  // namespace
+
+// Called once by rf2_plan_create: a score strip wider than the default dynamic-LDS limit needs the limit of
+// its kernel raised.  Doing it here keeps rf2_predict_mask free of anything but the launch (so it can be
+// recorded into a HIP graph).
+int rf2_mask_prepare(const rf2_plan* plan) {
+  const MaskLaunch m = mask_launch(plan);
+  if (m.lds > 48 * 1024)
+    RF2_HIP(hipFuncSetAttribute(m.kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)m.lds));
+  return RF2_OK;
+}
 
 extern "C" int rf2_predict_mask(const rf2_plan* plan, const float* qbar, const float* kbar, int32_t* blk_idx,
                                 int32_t* blk_cnt, uint8_t* mask_dense, float* scores, void* workspace,
@@ -185,29 +218,14 @@ extern "C" int rf2_predict_mask(const rf2_plan* plan, const float* qbar, const f
   if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
   const rf2_config& c = plan->cfg;
   const rf2_info& in = plan->info;
-  const int Tq = in.n_blocks, Tb = in.n_blocks_k;    // rows and columns of the block mask
-  const int E = (Tb + 63) / 64;
-  const int LD = E * 64 + 4;                        // +4: the 4 row groups of a tile store hit distinct banks
-  const size_t lds = (size_t)16 * LD * sizeof(float);
+  const MaskLaunch m = mask_launch(plan);
+  int Tq = in.n_blocks, Tk = in.n_blocks_k, LD = m.LD;   // rows and columns of the block mask
+  int rb = in.sink_block_begin, re = in.sink_block_end, cb = in.sink_block_begin_k, ce = in.sink_block_end_k;
+  int k_row = in.k_row, k_sel = in.k_sel;
+  float tau = c.cdf_threshold, scale_log2 = (float)(1.4426950408889634 / sqrt((double)c.head_dim));
+  void* args[] = {&qbar, &kbar, &blk_idx, &blk_cnt, &mask_dense, &scores, &Tq, &Tk, &LD, &rb, &re, &cb, &ce,
+                  &k_row, &k_sel, &tau, &scale_log2};
   const dim3 grid((Tq + 15) / 16, c.batch * c.heads, 1);
-  hipStream_t st = (hipStream_t)stream;
-  const bool cdf = (c.select_mode == RF2_SELECT_CDF);
-  const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)c.head_dim));
-#define RF2_MASK_CASE(DD, EE)                                                                                   \
-  {                                                                                                             \
-    auto kern = cdf ? predict_mask_kernel<DD, EE, true> : predict_mask_kernel<DD, EE, false>;                   \
-    if (lds > 48 * 1024)                                                                                        \
-      RF2_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));    \
-    kern<<<grid, 256, lds, st>>>(qbar, kbar, blk_idx, blk_cnt, mask_dense, scores, Tq, Tb, LD,                 \
-                                 in.sink_block_begin, in.sink_block_end, in.sink_block_begin_k,               \
-                                 in.sink_block_end_k, in.k_row, in.k_sel, c.cdf_threshold, scale_log2);       \
-    RF2_LAUNCH_CHECK();                                                                                         \
-    return RF2_OK;                                                                                              \
-  }
-  if (c.head_dim == 128) {
-    if (E <= 16) RF2_MASK_CASE(128, 16) else RF2_MASK_CASE(128, 32)
-  } else {
-    if (E <= 16) RF2_MASK_CASE(64, 16) else RF2_MASK_CASE(64, 32)
-  }
-#undef RF2_MASK_CASE
+  RF2_HIP(hipLaunchKernel(m.kernel, grid, dim3(256), args, m.lds, (hipStream_t)stream));
+  return RF2_OK;
 }

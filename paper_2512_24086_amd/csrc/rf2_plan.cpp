@@ -222,6 +222,8 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
     rf2_plan_destroy(p);
     return rc;
   }
+  const int prep = rf2_mask_prepare(p);
+  if (prep != RF2_OK) { rf2_plan_destroy(p); return prep; }
   *out = p;
   return RF2_OK;
 }
