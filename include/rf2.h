@@ -11,6 +11,7 @@
  *                         selection, plus the first-frame sink of Sec. 3.4
  *   rf2_block_sparse_attn Sec. 3.1, eqs. (1)-(4) with the block skip rule
  *   rf2_unpermute         inverse of the Sec. 3.3 permutation
+ *   (rf2_block_sparse_attn_unpermuted does the last two in one kernel.)
  *
  * Conventions
  *   - Every function returns an int: RF2_OK (0) or a negative RF2_ERR_* code.
@@ -27,8 +28,12 @@
  *   - A plan is immutable after creation; calls sharing a plan may run
  *     concurrently on different streams.
  *
- * Notation: B batch, Hh heads, d head_dim, N = T*H*W tokens, b block size
- * (b_q = b_k = b), Tb = ceil(N/b) blocks, N_pad = Tb*b.
+ * Notation: B batch, Hh heads, d head_dim, N = T*H*W (+ text_tokens) tokens, b block
+ * size, Tb = ceil(N/b) blocks, N_pad = Tb*b.  Q blocks have b = `block` rows; K and V
+ * blocks have `block_k` rows when that is set (b_q != b_k): then every K-side quantity
+ * -- kp, vp, kbar, the entries of the block lists, the columns of the block mask, the
+ * count that flags a dense row -- uses b = block_k and Tb = rf2_info.n_blocks_k, and
+ * the block mask is n_blocks x n_blocks_k.
  */
 #ifndef RF2_H
 #define RF2_H
