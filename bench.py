@@ -28,7 +28,7 @@ METRIC = "ms/layer + effective TFLOPS of block-sparse attn @80% sparsity, 75.6K 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 # HBM bytes per launch of the attention kernel on the headline workload, from the rocprofv3 --pmc
 # runs summarised in profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel); None = not measured.
-ATTN_TRAFFIC_BYTES = {"video720p": 1.28e11}   # profiles/block_sparse_attn_video720p.md
+ATTN_TRAFFIC_BYTES = {"video720p": 1.35e11}   # profiles/block_sparse_attn_video720p.md
 
 
 def ensure_library():
