@@ -38,6 +38,9 @@ SMALL = {
     "q256_single_block": (inputs.Workload("q256one", 20, 1, 1, 128, 1, 9, 11, 256, 0.5, 0, 0.3), dict(block_k=128)),
     "q256_k128_cdf_text": (inputs.Workload("q256cdf", 21, 1, 2, 128, 6, 12, 16, 256, 0.5, 1, 0.3, text_tokens=70),
                            dict(block_k=128, cdf_threshold=0.8)),
+    # two sink frames (2-D windows frame by frame), a window that does not divide the body; third budget reading
+    "two_sink_frames": (inputs.Workload("sink2", 24, 1, 2, 64, 7, 10, 13, 64, 0.3, 2, 0.3), dict(window=(2, 4, 8))),
+    "row_plus_sink": (inputs.WORKLOADS["tiny"], dict(budget_mode=2, sparsity=0.7)),
     "q64_k128_sink_front": (inputs.Workload("q64front", 22, 1, 2, 128, 4, 9, 11, 64, 0.6, 1, 0.3),
                             dict(block_k=128, sink_at_end=0)),
 }
@@ -308,6 +311,46 @@ def test_token_major_layout_gives_identical_results(name):
     assert torch.equal(o_fused.view(torch.int16), buf_b["o"].view(torch.int16))
     plan_a.close()
     plan_b.close()
+
+
+@pytest.mark.parametrize("layout", ["BHND", "BNHD"])
+def test_batch_of_two(layout):
+    """B = 2, three heads, ragged last block: every (batch, head) slice against the oracle, in both
+    memory orders, through the fused and the unfused exit."""
+    from paper_2512_24086_amd import rf2
+    wl = inputs.Workload("batch2", 23, 2, 3, 128, 4, 9, 11, 128, 0.5, 1, 0.3, text_tokens=5)
+    q, k, v = inputs.make_qkv(wl)
+    assert not torch.equal(q[0], q[1])
+    token_major = layout == "BNHD"
+    plan = hp.make_plan(wl, qkv_layout=rf2.RF2_LAYOUT_BNHD if token_major else rf2.RF2_LAYOUT_BHND)
+    dev = [x.to(DEV) for x in (q, k, v)]
+    if token_major:
+        dev = [x.transpose(1, 2).contiguous() for x in dev]
+    buf = plan.alloc(DEV, lse=True)
+    o_fused = plan.layer_fused(*dev, buf).clone()           # inverse permutation in the attention epilogue
+    buf["o"].fill_(float("nan"))
+    plan.layer(*dev, buf)                                   # attention into op, then rf2_unpermute
+    torch.cuda.synchronize()
+    assert torch.equal(o_fused.view(torch.int16), buf["o"].view(torch.int16))
+    o = o_fused.transpose(1, 2) if token_major else o_fused
+    i = plan.info
+    for b in range(wl.batch):
+        for h in range(wl.heads):
+            Q, K, V = (hp.f64(x[b, h]) for x in (q, k, v))
+            r = orc.layer(Q, K, V, T=wl.T, H=wl.H, W=wl.W, block=wl.block, sparsity=wl.sparsity,
+                          sink_frames=wl.sink_frames, window=(i.wt, i.wh, i.ww), text_tokens=wl.text_tokens)
+            M = hp.gpu_lists_to_mask(buf["blk_idx"][b, h], buf["blk_cnt"][b, h], i.n_blocks)
+            firm = r["gap"] > hp.TIE_GAP
+            assert np.array_equal(M[firm], r["M"][firm]), (b, h)
+            if not np.array_equal(M, r["M"]):               # a near-tie row differs: compare on the GPU's own mask
+                Qp, Kp, Vp = r["Qp"], r["Kp"], r["Vp"]
+                want = orc.unpermute(orc.block_sparse_attention(Qp, Kp, Vp, M, wl.block), r["perm"])
+            else:
+                want = r["O"]
+            err = np.abs(hp.f64(o[b, h]) - want)
+            assert err.max() <= hp.ATTN_MAX_ABS and err.mean() <= hp.ATTN_MEAN_ABS, (b, h, err.max(), err.mean())
+            assert np.array_equal(hp.f64(buf["qp"][b, h])[:wl.N], r["Qp"]), (b, h)
+    plan.close()
 
 
 def test_measured_peaks_are_plausible():
