@@ -1,10 +1,10 @@
 // Block-sparse flash attention (Sec. 3.1, eqs. 1-4 with the block skip rule) for gfx950.
 //
 // One workgroup owns one Q block (b_q rows) of one (batch, head) and walks that row's list of
-// kept K/V blocks (b_k rows each; b_q and b_k may differ).  Every wavefront owns 32 query rows and sees all keys, so there is nothing
-// to merge at the end; a workgroup needs at most 80 KiB of LDS and 256 registers per lane, so
-// two workgroups share a compute unit (two wavefronts per SIMD) and each hides the barriers,
-// LDS latencies and vector-ALU phases of the other.
+// kept K/V blocks (b_k rows each; b_q and b_k may differ).  Every wavefront owns 32 query rows
+// and sees all keys, so there is nothing to merge at the end; a workgroup needs at most 80 KiB of
+// LDS and 256 registers per lane, so two workgroups share a compute unit (two wavefronts per
+// SIMD) and each hides the barriers, LDS latencies and vector-ALU phases of the other.
 //
 // Both products are computed transposed so that no register shuffling is needed between them
 // (v_mfma_f32_32x32x16_bf16, D = A(32xk) * B(kx32) + C):
@@ -382,7 +382,8 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
       }
       if constexpr (ODD) {
         if (g < C::LPW) dma_one(v_dst + g * (C::NW * 1024), vbase + g * (C::NW * 1024), v_voff);
-        else if (g < 2 * C::LPW) dma_one(k_dst + (g - C::LPW) * (C::NW * 1024), kbase + (g - C::LPW) * (C::NW * 1024), k_voff);
+        else if (g < 2 * C::LPW)
+          dma_one(k_dst + (g - C::LPW) * (C::NW * 1024), kbase + (g - C::LPW) * (C::NW * 1024), k_voff);
       }
       // Slots stay in this order: the operand reads keep their PD-slot lead over the MFMAs that
       // consume them (left alone, the scheduler packs each read right in front of its consumer).

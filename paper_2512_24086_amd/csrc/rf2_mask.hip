@@ -1,8 +1,9 @@
 // Block-mask prediction: S_hat = qbar kbar^T (Sec. 3.2, eq. 7) in fp32 on the matrix cores,
 // then per-row top-n selection (eq. 8) with the first-frame sink (Sec. 3.4), fused in one
 // kernel.  A workgroup owns 16 rows (Q blocks) of one head: its 4 wavefronts first fill a 16 x Tk
-// score strip in LDS (Tk = number of K blocks; the mask is Tq x Tk, square unless b_q != b_k), then each wavefront selects 4 of the rows with a bitwise threshold
-// search over order-preserving integer keys and emits the ascending block list.
+// score strip in LDS (Tk = number of K blocks; the mask is Tq x Tk, square unless b_q != b_k),
+// then each wavefront selects 4 of the rows with a bitwise threshold search over
+// order-preserving integer keys and emits the ascending block list.
 // The cumulative-mass variant (RF2_SELECT_CDF) runs the same search on probability mass
 // instead of counts: the threshold is the largest key whose upper set carries >= tau of the
 // row's softmax mass.

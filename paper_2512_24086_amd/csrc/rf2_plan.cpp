@@ -116,7 +116,8 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
   in.last_block_valid_k = (int32_t)(N - (int64_t)(in.n_blocks_k - 1) * bk);
   in.wt = win.wt; in.wh = win.wh; in.ww = win.ww;
   const int Tb = in.n_blocks, Tk = in.n_blocks_k;       // rows and columns of the block mask
-  if (Tb > 2048 || Tk > 2048) { delete p; return RF2_ERR_UNSUPPORTED; }  // one row of block scores must fit the selection kernel's LDS
+  // one row of block scores must fit the selection kernel's LDS
+  if (Tb > 2048 || Tk > 2048) { delete p; return RF2_ERR_UNSUPPORTED; }
 
   // Always-dense blocks: every block that holds at least one sink-frame or text token (Sec. 3.4).
   const int64_t frame = (int64_t)c.H * c.W;
