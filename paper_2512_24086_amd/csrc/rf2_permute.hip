@@ -27,7 +27,15 @@ __global__ void __launch_bounds__(256) permute_pool_kernel(
   const int bh = blockIdx.y;
   const uint4* __restrict__ src = x + ((bh / heads) * st.batch + (bh % heads) * st.head) * CH;
   uint4* __restrict__ dst = xp + ((size_t)bh * n_blocks + blk) * BLK * CH;
-  const int c = threadIdx.x % CH, rg = threadIdx.x / CH;
+  // Q: CH neighbouring lanes move one row (row-major stores).  K: 8 neighbouring lanes move half a row
+  // (one 128-byte line) and a wavefront covers 8 rows x 8 chunks, so that its stores of a chunk
+  // column (8 consecutive rows x 16 bytes in the operand layout) are whole 128-byte lines too.
+  int c = threadIdx.x % CH, rg = threadIdx.x / CH;
+  if constexpr (IS_K && CH == 16) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    c = (lane & 7) + 8 * (wave & 1);
+    rg = (lane >> 3) + 8 * (wave >> 1);
+  }
 
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
