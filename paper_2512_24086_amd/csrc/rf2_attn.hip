@@ -96,9 +96,15 @@ __device__ __forceinline__ const unsigned char* uniform_ptr(const void* p) {
 
 // One wavefront-wide direct-to-LDS load: 64 x 16 B from g + voff (scalar base, per-lane 32-bit
 // byte offset) to the KiB of LDS at `lds_kib`.
+// M0 is written here and named as clobbered.  The compiler reserves M0 for itself (and says so with a
+// warning, silenced below): it sets M0 immediately in front of each of its own uses (LDS-direct builtins,
+// relative moves, message and GWS instructions), none of which this translation unit contains.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma_one(uint32_t lds_kib, const unsigned char* g, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_kib), "v"(voff), "s"(g) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_kib), "v"(voff), "s"(g) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // A whole part (LPW KiB per wavefront): wavefront w takes KiB u*NW + w for u = 0..LPW-1.
 template <int NW, int LPW>
@@ -517,7 +523,7 @@ int dispatch_blocks(const rf2_plan* plan, const void* qp, const void* kp, const 
 int dispatch_attn(const rf2_plan* plan, const void* qp, const void* kp, const void* vp, const int32_t* blk_idx,
                   const int32_t* blk_cnt, void* out, float* lse, bool scatter, void* stream) {
   if (!plan || !qp || !kp || !vp || !blk_idx || !blk_cnt || !out) return RF2_ERR_INVALID_ARG;
-  if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
+  if (const int rc = rf2_check_device(plan)) return rc;
   hipStream_t st = (hipStream_t)stream;
   if (plan->cfg.head_dim == 128) return dispatch_blocks<128>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);
   if (plan->cfg.head_dim == 64) return dispatch_blocks<64>(plan, qp, kp, vp, blk_idx, blk_cnt, out, lse, scatter, st);

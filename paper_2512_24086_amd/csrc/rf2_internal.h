@@ -41,5 +41,16 @@ int rf2_note_hip_error(hipError_t e);
     if (e__ != hipSuccess) return rf2_note_hip_error(e__); \
   } while (0)
 
+// Compute entry points run on the device the plan's tables live on: a plan without a device
+// cannot compute (RF2_ERR_HIP), and a call made while another device is current is rejected
+// (RF2_ERR_INVALID_ARG) instead of launching against the wrong GPU's tables.
+inline int rf2_check_device(const rf2_plan* plan) {
+  if (plan->device < 0) return rf2_note_hip_error(hipErrorNoDevice);
+  int current = -1;
+  const hipError_t e = hipGetDevice(&current);
+  if (e != hipSuccess) return rf2_note_hip_error(e);
+  return current == plan->device ? RF2_OK : RF2_ERR_INVALID_ARG;
+}
+
 // Launch check used after every kernel launch.
 #define RF2_LAUNCH_CHECK() RF2_HIP(hipGetLastError())

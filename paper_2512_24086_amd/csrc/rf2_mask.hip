@@ -216,7 +216,7 @@ extern "C" int rf2_predict_mask(const rf2_plan* plan, const float* qbar, const f
                                 void* stream) {
   (void)workspace;
   if (!plan || !qbar || !kbar || !blk_idx || !blk_cnt) return RF2_ERR_INVALID_ARG;
-  if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
+  if (const int rc = rf2_check_device(plan)) return rc;
   const rf2_config& c = plan->cfg;
   const rf2_info& in = plan->info;
   const MaskLaunch m = mask_launch(plan);

@@ -180,7 +180,7 @@ extern "C" int rf2_permute(const rf2_plan* plan, const void* q, const void* k, c
                            void* vp, float* qbar, float* kbar, void* stream) {
   if (!plan || !q || !k || !v || !qp || !kp || !vp) return RF2_ERR_INVALID_ARG;
   if ((qbar == nullptr) != (kbar == nullptr)) return RF2_ERR_INVALID_ARG;
-  if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
+  if (const int rc = rf2_check_device(plan)) return rc;
   hipStream_t st = (hipStream_t)stream;
   if (plan->cfg.head_dim == 128) return permute_for_dim<128>(plan, q, k, v, qp, kp, vp, qbar, kbar, st);
   if (plan->cfg.head_dim == 64) return permute_for_dim<64>(plan, q, k, v, qp, kp, vp, qbar, kbar, st);
@@ -189,7 +189,7 @@ extern "C" int rf2_permute(const rf2_plan* plan, const void* q, const void* k, c
 
 extern "C" int rf2_unpermute(const rf2_plan* plan, const void* op, void* o, void* stream) {
   if (!plan || !op || !o) return RF2_ERR_INVALID_ARG;
-  if (plan->device < 0) { rf2_note_hip_error(hipErrorNoDevice); return RF2_ERR_HIP; }
+  if (const int rc = rf2_check_device(plan)) return rc;
   const rf2_config& c = plan->cfg;
   const rf2_info& in = plan->info;
   hipStream_t st = (hipStream_t)stream;

@@ -168,6 +168,24 @@ def test_cdf_selection_closed_cases():
         orc.select_blocks_cdf(S, 1.0, d, 8, 10)
 
 
+def test_cdf_margin_by_hand():
+    """Block probabilities 0.4, 0.3, 0.2, 0.1 (scores 2 ln p with d = 4): cumulative 0.4, 0.7, 0.9, 1.
+    The margin is the distance from tau to the nearer of the cumulative values just before and just
+    after the last column taken; each side decides in one of the cases below."""
+    S = 2.0 * np.log(np.array([[0.2, 0.4, 0.1, 0.3]]))       # descending order: columns 1, 3, 0, 2
+    for tau, kept, margin in ((0.75, [1, 3, 0], 0.05),       # 0.7 < tau <= 0.9: the side before the cut (0.75 - 0.7)
+                              (0.65, [1, 3], 0.05),          # 0.4 < tau <= 0.7: the side after it (0.7 - 0.65)
+                              (0.85, [1, 3, 0], 0.05),       # after: 0.9 - 0.85 (before: 0.15)
+                              (0.45, [1, 3], 0.05),          # before: 0.45 - 0.4 (after: 0.25)
+                              (0.05, [1], 0.05),             # one column: before = the empty sum 0
+                              (0.39, [1], 0.01)):            # one column, after: 0.4 - 0.39
+        M, m = orc.select_blocks_cdf(S, tau, 4, 0, 0)
+        assert np.flatnonzero(M[0]).tolist() == sorted(kept), tau
+        assert abs(m[0] - margin) < 1e-12, (tau, m[0])
+    M, m = orc.select_blocks_cdf(S, 0.95, 4, 0, 0)           # everything taken: no cut, no margin
+    assert M.all() and m[0] == np.inf
+
+
 def test_layer_with_cdf_selection_equals_library_masked_attention():
     import torch
     rng = np.random.default_rng(21)

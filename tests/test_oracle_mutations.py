@@ -11,7 +11,7 @@ from tests import test_oracle_perm as t_perm
 
 REAL = {n: getattr(orc, n) for n in ("perm_table", "inverse_table", "unpermute", "sink_block_range", "budget",
                                      "pool_blocks", "block_scores", "select_blocks", "select_blocks_cdf",
-                                     "block_sparse_attention", "selection_gap", "kept_pairs")}
+                                     "block_sparse_attention", "selection_gap", "kept_pairs", "default_window")}
 
 
 def _perm_sink_front(*a, **k):                      # ignores "first frame moved to the end"
@@ -97,6 +97,25 @@ def _cdf_forgets_sqrt_d(S, tau, d, *a, **k):
     return REAL["select_blocks_cdf"](S, tau, 1, *a, **k)
 
 
+def _cdf_margin_one_sided(side):
+    """The margin computed from one side of the cut only (the other side forgotten)."""
+    def mutant(S, tau, d, sb, se, sink_k=None):
+        M, margin = REAL["select_blocks_cdf"](S, tau, d, sb, se, sink_k)
+        kb, ke = (sb, se) if sink_k is None else sink_k
+        cand = np.array([j for j in range(S.shape[1]) if not (kb <= j < ke)])
+        for i in np.flatnonzero(np.isfinite(margin)):
+            p = np.exp((S[i, cand] - S[i, cand].max()) / np.sqrt(d))
+            cum = np.cumsum(np.sort(p / p.sum())[::-1])
+            n = int(M[i, cand].sum())
+            margin[i] = abs(cum[n - 1] - tau) if side == "after" else abs(tau - (cum[n - 2] if n >= 2 else 0.0))
+        return M, margin
+    return mutant
+
+
+def _window_256_keeps_the_128_shape(block, video):
+    return REAL["default_window"](min(block, 128), video)
+
+
 def _call_all(tests):
     """Runs pin tests (plain functions, with their parameter sets); returns True if any of them fails."""
     for fn, argsets in tests:
@@ -138,6 +157,10 @@ MUTANTS = {
     "wrong final normaliser": ("block_sparse_attention", _attn_wrong_normaliser, [(t_attn.test_constant_and_one_hot_values, [()])]),
     "cdf normalises over sink columns too": ("select_blocks_cdf", _cdf_normalises_over_all_columns,
                                              [(t_mask.test_cdf_selection_vs_loops, [(12, 9, 12, 0.5), (17, 14, 17, 0.97)])]),
+    "cdf margin looks only after the cut": ("select_blocks_cdf", _cdf_margin_one_sided("after"), [(t_mask.test_cdf_margin_by_hand, [()])]),
+    "cdf margin looks only before the cut": ("select_blocks_cdf", _cdf_margin_one_sided("before"), [(t_mask.test_cdf_margin_by_hand, [()])]),
+    "256-token blocks get the 128-token window": ("default_window", _window_256_keeps_the_128_shape,
+                                                  [(t_perm.test_interior_window_is_one_block, [()])]),
     "cdf forgets 1/sqrt(d)": ("select_blocks_cdf", _cdf_forgets_sqrt_d, [(t_mask.test_cdf_selection_vs_loops, [(12, 9, 12, 0.5), (12, 0, 0, 0.9)])]),
 }
 

@@ -98,8 +98,14 @@ def test_interior_window_is_one_block():
     blk = perm[:b]                       # first window of the body (frames 1,2)
     t, h, w = blk // (H * W), (blk // W) % H, blk % W
     assert set(t) == {1, 2} and h.max() - h.min() == wh - 1 and w.max() - w.min() == ww - 1
-    for blk_sz, vid in [(128, True), (128, False), (64, True), (64, False)]:
-        assert np.prod(orc.default_window(blk_sz, vid)) == blk_sz
+    for blk_sz, vid in [(256, True), (256, False), (128, True), (128, False), (64, True), (64, False)]:
+        win = orc.default_window(blk_sz, vid)
+        assert np.prod(win) == blk_sz and (vid or win[0] == 1)
+        # the first interior window fills exactly the first block: a box of the window's shape
+        Tg, Hg, Wg = (2 * win[0] if vid else 1), 2 * win[1], 2 * win[2]
+        first = orc.perm_table(Tg, Hg, Wg, *win)[:blk_sz]
+        t, h, w = first // (Hg * Wg), (first // Wg) % Hg, first % Wg
+        assert (t.max() + 1, h.max() + 1, w.max() + 1) == win and len(set(first.tolist())) == blk_sz
 
 
 def test_round_trip_is_identity():
