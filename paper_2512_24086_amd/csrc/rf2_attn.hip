@@ -16,12 +16,12 @@
 // group in the order 0-3, 8-11, 4-7, 12-15 -- the order rf2_permute writes.  Row statistics are
 // per lane (one query column) plus one exchange with lane l^32.
 //
-// Softmax (eqs. 2, 3) without a per-unit row maximum: every S^T accumulator chain starts from the
-// tile -m_ref (the addend operand of its first MFMA), so the accumulators hold q.k - m_ref directly.
-// m_ref is set exactly from the first unit of the row and afterwards only moved when the row sum of
-// a unit leaves the range fp32/bf16 carry without loss (> 2^40, or not finite); the final division
-// by the row sum makes the reference point irrelevant.  The common path is one multiply, one exp2,
-// one add and half a bf16 pack per probability.
+// Softmax (eqs. 2, 3) without a per-unit row maximum: a probability is exp2(fma(q.k, c, -m_ref c))
+// with c = log2(e)/sqrt(d), the subtraction of eq. (2) riding on the multiply-add that applies the
+// scale.  m_ref is set exactly from the first unit of the row and afterwards only moved when the row
+// sum of a unit leaves the range fp32/bf16 carry without loss (> 2^40, or not finite); the final
+// division by the row sum makes the reference point irrelevant.  The common path is one fused
+// multiply-add, one exp2, one add and half a bf16 pack per probability.
 //
 // The loop is software-pipelined over "units" (one 32-key tile; a 64-key part of a K/V block is
 // two units): step s issues the matrix products S_{s+1} and O += V P_{s-1} around the softmax
@@ -68,19 +68,22 @@ struct AttnCfg {
 // The S^T product is issued through assembly so that its accumulators are ordinary vector
 // registers that the softmax arithmetic reads in place.  The compiler does not know these
 // statements are MFMAs, so what it would do for an MFMA is done by hand:
-//  * the wait states between the last MFMA of a chain and the first vector-ALU read of its result
-//    are part of qk_last (18 >= the 12 an 8-pass MFMA needs here);
-//  * the addend tile of qk_first is read by the matrix core over several passes after issue; it is
-//    declared read-write so the compiler keeps it in place and never hands its registers to a
-//    following instruction while the MFMA is in flight;
+//  * between the last MFMA of a chain and the first vector-ALU read of its result lie the wait states
+//    an 8-pass MFMA needs.  In the loop the chain ends in slot NQ-1 of a step and its accumulators are
+//    first read in the following step, behind the NP matrix products of the remaining slots (their
+//    order is frozen by the scheduling barriers), so nothing is added there; the chain of the
+//    prologue is followed by code the compiler orders freely and ends in qk_last_wait, which carries
+//    the wait states itself (18 >= the 12 needed);
+//  * the first MFMA of a chain takes the constant 0 as its addend, so no register is read by the
+//    matrix core after issue except the A and B operands;
 //  * A and B operands are read at issue; they come from LDS reads and the resident Q fragments.
-__device__ __forceinline__ void qk_first(f32x16& S, const bf16x8& a, const bf16x8& b, f32x16& addend) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %2, %3, %1" : "=&v"(S), "+v"(addend) : "v"(a), "v"(b));
+__device__ __forceinline__ void qk_first(f32x16& S, const bf16x8& a, const bf16x8& b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void qk_next(f32x16& S, const bf16x8& a, const bf16x8& b) {
   asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S) : "v"(a), "v"(b));
 }
-__device__ __forceinline__ void qk_last(f32x16& S, const bf16x8& a, const bf16x8& b) {
+__device__ __forceinline__ void qk_last_wait(f32x16& S, const bf16x8& a, const bf16x8& b) {
   asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\t"
       "s_nop 7\n\ts_nop 7\n\ts_nop 1"
       : "+v"(S)
@@ -145,27 +148,18 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
   constexpr uint32_t VRING = C::NK * C::PART_BYTES;
 
   // ---- which Q block ---------------------------------------------------------------
-  // Slots of an XCD, in issue order: the all-column sink rows are several times longer than
-  // ordinary rows, so the sink rows of head h are issued LEAD heads ahead of its ordinary rows
-  // (sink(0..LEAD-1), then sink(h+LEAD), plain(h) for each h, then the last plain rows): no long
-  // row is left running alone at the end, while only a few heads' K/V are live at a time.
+  // Slots of an XCD, in issue order: the all-column sink rows of every head first, then the ordinary
+  // rows head by head.  A sink row is several times longer than an ordinary one; issued first (longest
+  // jobs first) none of them is left running alone at the end, and the short rows fill the tail evenly.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int lead = min(2, n_bh), both = sink_per_xcd + plain_per_xcd;
   int bh, entry;
-  if (slot < lead * sink_per_xcd) {
+  if (slot < n_bh * sink_per_xcd) {
     bh = slot / sink_per_xcd;
     entry = slot % sink_per_xcd;
   } else {
-    const int t = slot - lead * sink_per_xcd;
-    if (t < (n_bh - lead) * both) {
-      const int ph = t / both, r = t % both;
-      bh = r < sink_per_xcd ? ph + lead : ph;
-      entry = r;
-    } else {
-      const int u = t - (n_bh - lead) * both;
-      bh = n_bh - lead + u / plain_per_xcd;
-      entry = sink_per_xcd + u % plain_per_xcd;
-    }
+    const int t = slot - n_bh * sink_per_xcd;
+    bh = t / plain_per_xcd;
+    entry = sink_per_xcd + t % plain_per_xcd;
   }
   // The work table deals a head's rows to 8 shares of slightly different size (e.g. 29 sink rows:
   // five shares of 4, three of 3); the share an XCD takes rotates with the head so that no XCD
@@ -220,13 +214,10 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
   for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
-  // Softmax reference m_ref (per query column, in units of the raw products q.k) and the addend tile
-  // negm = -m_ref every accumulator chain starts from.  l_run lags one unit behind: rs_last, the row
-  // sum of the latest unit, is still to be added.
-  float m_ref = 0.f, l_run = 0.f, rs_last = 0.f;
-  f32x16 negm;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) negm[i] = 0.f;
+  // Softmax reference m_ref (per query column, in units of the raw products q.k) and nmc = -m_ref * c,
+  // the addend of the multiply-add in front of every exp2.  l_run lags one unit behind: rs_last, the
+  // row sum of the latest unit, is still to be added.
+  float m_ref = 0.f, nmc = 0.f, l_run = 0.f, rs_last = 0.f;
 
   // ---- building blocks ------------------------------------------------------------------
   // One step has NQ + NP "slots" of one MFMA each: slots 0..NQ-1 are the k-steps of
@@ -255,14 +246,13 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
     return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
   };
   // Moves the reference by delta (per query column): everything accumulated so far is rescaled
-  // (eqs. 3, 4) and the accumulator tiles that were started from the old reference are shifted.
-  auto move_reference = [&](float delta, f32x16& Sx, f32x16& Sy) {
+  // (eqs. 3, 4).  The accumulators hold raw products, so nothing else changes.
+  auto move_reference = [&](float delta) {
     // (the very first move may go down; nothing has been accumulated then, any finite factor will do)
     const float alpha = __builtin_amdgcn_exp2f(-fmaxf(delta, 0.f) * scale_log2);
     m_ref += delta;
+    nmc = -m_ref * scale_log2;
     l_run *= alpha;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { negm[i] = -m_ref; Sx[i] -= delta; Sy[i] -= delta; }
 #pragma unroll
     for (int dt = 0; dt < C::DT; ++dt)
 #pragma unroll
@@ -270,14 +260,14 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
   };
   // The probabilities P of the unit whose accumulators are in S were out of range; O holds all
   // earlier units, so the reference moves up and P (and rs_last) are recomputed.
-  auto redo_unit = [&](f32x16& S, f32x16& Sother, bf16x8 (&P)[2]) {
+  auto redo_unit = [&](f32x16& S, bf16x8 (&P)[2]) {
     const float mx = rowmax(S);
-    move_reference(mx > 0.f ? mx : 0.f, S, Sother);
+    move_reference(mx > m_ref ? mx - m_ref : 0.f);
     rs_last = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; i += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(S[i] * scale_log2);
-      const float p1 = __builtin_amdgcn_exp2f(S[i + 1] * scale_log2);
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(S[i], scale_log2, nmc));
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(S[i + 1], scale_log2, nmc));
       const bf16x2 pk = {(__bf16)p0, (__bf16)p1};
       rs_last += p0 + p1;
       P[i / 8][i % 8] = pk[0];
@@ -288,7 +278,7 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
   // buffer this step overwrites), the first unit (sets the reference exactly), and the units of the
   // ragged last block (keys past the end of the sequence are masked here).
   auto pre_step = [&](f32x16& S, f32x16& Sprev, bf16x8 (&Pprev)[2], uint32_t v_addr, int s, bool redo) {
-    if (redo) redo_unit(Sprev, S, Pprev);
+    if (redo) redo_unit(Sprev, Pprev);
     if (s == 0 || s >= partial_begin) {
       // the pending product V P_{s-1} must reach O before O is rescaled; it is then neutralised
 #pragma unroll
@@ -310,11 +300,11 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
       }
       const float mx = rowmax(S);
       // first unit: exact reference (it has at least one valid key); later: only upwards
-      const bool move = (s == 0) ? true : (mx > 0.f);
+      const bool move = (s == 0) ? true : (mx > m_ref);
       if (__builtin_amdgcn_ballot_w64(move) != 0ull) {
         l_run += rs_last;                                  // unit s-1 is in O now: rescale it with the rest
         rs_last = 0.f;
-        move_reference(move ? mx : 0.f, S, Sprev);
+        move_reference(move ? mx - m_ref : 0.f);
       }
     }
   };
@@ -360,9 +350,8 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
 #pragma unroll
     for (int g = 0; g < NSLOT; ++g) {
       if (g + PD < NSLOT) opnd[g + PD] = operand(k_addr, v_addr, g + PD);
-      if (g == 0) qk_first(Snext, opnd[g], qf[g], negm);
-      else if (g < NQ - 1) qk_next(Snext, opnd[g], qf[g]);
-      else if (g == NQ - 1) qk_last(Snext, opnd[g], qf[g]);
+      if (g == 0) qk_first(Snext, opnd[g], qf[g]);
+      else if (g < NQ) qk_next(Snext, opnd[g], qf[g]);
       else {
         const int dt = (g - NQ) / 2, ks = (g - NQ) % 2;
         o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[g], Pprev[ks], o[dt], 0, 0, 0);
@@ -377,8 +366,8 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
           Pcur[(i - 2) / 8][(i - 2) % 8] = pk[0];
           Pcur[(i - 2) / 8][(i - 2) % 8 + 1] = pk[1];
         }
-        e0 = __builtin_amdgcn_exp2f(Scur[i] * scale_log2);
-        e1 = __builtin_amdgcn_exp2f(Scur[i + 1] * scale_log2);
+        e0 = __builtin_amdgcn_exp2f(fmaf(Scur[i], scale_log2, nmc));
+        e1 = __builtin_amdgcn_exp2f(fmaf(Scur[i + 1], scale_log2, nmc));
         if (i == 14) {
           const bf16x2 pk = {(__bf16)e0, (__bf16)e1};
           rs += e0 + e1;
@@ -423,9 +412,9 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
 #pragma unroll
     for (int ds = 0; ds < C::DS; ++ds) {
       const bf16x8 a = k_operand(k_lane, ds);
-      if (ds == 0) qk_first(Sa, a, qf[ds], negm);
+      if (ds == 0) qk_first(Sa, a, qf[ds]);
       else if (ds < C::DS - 1) qk_next(Sa, a, qf[ds]);
-      else qk_last(Sa, a, qf[ds]);
+      else qk_last_wait(Sa, a, qf[ds]);
     }
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
@@ -451,7 +440,7 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
     }
     // ---- last product: O += V P_{U-1} (tile 1 of the last part; P_{U-1} is in Pb) ---------------
     ring_barrier<0>();
-    if (redo) redo_unit(Sb, Sa, Pb);
+    if (redo) redo_unit(Sb, Pb);
     l_run += rs_last;
     {
       const uint32_t v_addr = VRING + (uint32_t)(vm * C::PART_BYTES) + V_TILE + v_lane;
