@@ -26,9 +26,32 @@ from paper_2512_24086_amd import inputs, rf2  # noqa: E402
 
 METRIC = "ms/layer + effective TFLOPS of block-sparse attn @80% sparsity, 75.6K tokens"
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
-# HBM bytes per launch of the attention kernel on the headline workload, from the rocprofv3 --pmc
-# runs summarised in profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel); None = not measured.
-ATTN_TRAFFIC_BYTES = {"video720p": 1.35e11}   # profiles/block_sparse_attn_video720p.md
+# HBM/fabric bytes per launch of the attention kernel come from rocprofv3 --pmc runs (FETCH_SIZE and
+# WRITE_SIZE, scaled by a copy kernel of known size).  They are kept in a small table beside the profile
+# summaries, one line per measurement: workload, hash of the kernel source it was measured on, bytes.
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "attn_traffic.txt")
+ATTN_SOURCE = os.path.join(ROOT, "paper_2512_24086_amd", "csrc", "rf2_attn.hip")
+
+
+def attn_source_hash() -> str:
+    import hashlib
+    with open(ATTN_SOURCE, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
+
+
+def measured_traffic(workload: str):
+    """Bytes per launch measured for `workload` on exactly the kernel source that is in the tree, else None
+    (a figure measured on another version of the kernel says nothing about this one)."""
+    try:
+        here = attn_source_hash()
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                cols = line.split()
+                if len(cols) >= 3 and not line.startswith("#") and cols[0] == workload and cols[1] == here:
+                    return float(cols[2])
+    except OSError:
+        pass
+    return None
 
 
 def ensure_library():
@@ -87,23 +110,62 @@ def time_attn_only(plan, buf, idx, cnt, iters, warmup=1):
     return a.elapsed_time(b) / iters
 
 
-def time_sdpa(q, k, v, iters=2):
-    """Library dense attention on the same GPU (context for the dense side of the speedup)."""
-    try:
-        f = torch.nn.functional.scaled_dot_product_attention
-        f(q, k, v)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(iters):
-            f(q, k, v)
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / iters
-    except Exception as e:  # noqa: BLE001 -- report, never fail the bench on the context number
-        return f"unavailable: {type(e).__name__}"
+def time_sdpa(q, k, v, iters=5):
+    """Library dense attention on the same GPU (context for the dense side of the speedup): every fused
+    backend of torch's scaled_dot_product_attention that accepts the problem is timed by name; returns
+    (best time in ms, name of that backend, {name: ms or reason})."""
+    from torch.nn.attention import SDPBackend, sdpa_kernel
+    f = torch.nn.functional.scaled_dot_product_attention
+    tried = {}
+    for backend in (SDPBackend.FLASH_ATTENTION, SDPBackend.EFFICIENT_ATTENTION):
+        try:
+            with sdpa_kernel(backend):
+                f(q, k, v)
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(iters):
+                    f(q, k, v)
+                b.record()
+                torch.cuda.synchronize()
+                tried[backend.name] = a.elapsed_time(b) / iters
+        except Exception as e:  # noqa: BLE001 -- report, never fail the bench on the context number
+            tried[backend.name] = f"unavailable: {type(e).__name__}"
+    timed = {n: t for n, t in tried.items() if isinstance(t, float)}
+    if not timed:
+        return None, None, tried
+    best = min(timed, key=timed.get)
+    return timed[best], best, tried
 
 
-def cpu_baseline(wl, plan, q, k, v, dense_flops):
+def mask_diagnostics(orc, plan, buf, head, Qp, Kp, S_hat, M):
+    """Near-tie rows of one head (selection-boundary gap <= 1e-3 in the oracle's scores: the rows where
+    several masks are correct), how many of them the GPU resolved differently, and the share of the dense
+    attention mass the mask keeps on 256 seeded query rows."""
+    import numpy as np
+    i, c = plan.info, plan.cfg
+    Tq, Tk = i.n_blocks, i.n_blocks_k
+    idx, cnt = buf["blk_idx"][0, head].cpu().numpy(), buf["blk_cnt"][0, head].cpu().numpy()
+    M_gpu = np.zeros((Tq, Tk), dtype=bool)
+    for r in range(Tq):
+        if cnt[r] == Tk:
+            M_gpu[r] = True
+        else:
+            M_gpu[r, idx[r, :cnt[r]]] = True
+    out = {"head": head}
+    if c.select_mode == rf2.RF2_SELECT_TOPN:
+        gap = orc.selection_gap(S_hat, i.k_sel, i.sink_block_begin, i.sink_block_end,
+                                (i.sink_block_begin_k, i.sink_block_end_k))
+        near = gap <= 1e-3
+        out.update({"near_tie_rows": int(near.sum()), "rows": int(np.isfinite(gap).sum()),
+                    "near_tie_rows_resolved_differently": int((M_gpu[near] != M[near]).any(axis=1).sum()),
+                    "other_rows_differing": int((M_gpu[~near] != M[~near]).any(axis=1).sum())})
+    rows = np.sort(np.random.default_rng(0).choice(int(i.N), min(256, int(i.N)), replace=False))
+    out["dense_attention_mass_kept"] = round(orc.attention_mass_recall(Qp, Kp, M_gpu, c.block, i.block_k, rows), 4)
+    out["kept_density"] = round(float(M_gpu[rows // c.block].mean()), 4)
+    return out
+
+
+def cpu_baseline(wl, plan, q, k, v, buf, dense_flops):
     """The fp64 oracle, untuned, on a bounded sample: all stages for ONE head up to the mask, attention
     for the Q blocks of that head; extrapolated to the whole layer by head count and kept pairs."""
     from oracle import rf2_oracle as orc
@@ -122,6 +184,7 @@ def cpu_baseline(wl, plan, q, k, v, dense_flops):
     else:
         M = orc.select_blocks(S_hat, i.k_sel, i.sink_block_begin, i.sink_block_end, sink_k)
     t_pre = time.perf_counter() - t0
+    diag = mask_diagnostics(orc, plan, buf, head, Qp, Kp, S_hat, M)
     Tb = i.n_blocks
     sample = list(range(Tb))                           # every Q block of this one head: ~10 s of oracle time
     t0 = time.perf_counter()
@@ -135,7 +198,7 @@ def cpu_baseline(wl, plan, q, k, v, dense_flops):
     layer_s = per_head * c.batch * c.heads
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {"value": dense_flops / layer_s / 1e12, "unit": "TFLOP/s dense-equivalent (extrapolated)",
-            "cores": threads, "kind": "oracle", "ms_per_layer_extrapolated": layer_s * 1e3,
+            "cores": threads, "kind": "oracle", "ms_per_layer_extrapolated": layer_s * 1e3, "mask": diag,
             "sample": f"head {head}: permute+pool+scores+selection in full ({t_pre:.2f} s), attention on "
                       f"{len(sample)} of {Tb} Q blocks = {pairs} block pairs ({t_attn:.2f} s), scaled by "
                       f"kept pairs and by {c.batch * c.heads} heads"}
@@ -195,7 +258,10 @@ def main():
     attn_ms = stages["block_sparse_attn"]
     itemsize = 2
     tensor_bytes = bh * wl.N * wl.head_dim * itemsize
-    gbps = {"permute_pool": (6 * tensor_bytes) / (stages["permute_pool"] * 1e-3) / 1e9}
+    # permute + pool: reads q, k, v; writes the padded permuted copies and the fp32 block means
+    permute_bytes = (3 * tensor_bytes + bh * wl.head_dim * itemsize * (i.N_pad + 2 * i.N_pad_k)
+                     + bh * wl.head_dim * 4 * (i.n_blocks + i.n_blocks_k))
+    gbps = {"permute_pool": permute_bytes / (stages["permute_pool"] * 1e-3) / 1e9}
     if args.unfused:
         gbps["unpermute"] = (2 * tensor_bytes) / (stages["unpermute"] * 1e-3) / 1e9
     else:
@@ -227,20 +293,24 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "block_sparse_attn_kernel",
                      "achieved": kept_flops / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": kept_flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                     "traffic": (ATTN_TRAFFIC_BYTES.get(wl.name)
+                     "traffic": (measured_traffic(wl.name)
                                  if args.sparsity is None and not wl.text_tokens and args.cdf is None
                                  and not args.head_dim and not args.block and not args.block_k else None)},
     }
     if not args.no_dense:
         cnt_dense = torch.full_like(buf["blk_cnt"], i.n_blocks_k)
-        dense_ms = time_attn_only(plan, buf, buf["blk_idx"], cnt_dense, iters=2)
-        sdpa_ms = time_sdpa(q, k, v)
-        best = min(dense_ms, sdpa_ms) if isinstance(sdpa_ms, float) else dense_ms
+        dense_ms = time_attn_only(plan, buf, buf["blk_idx"], cnt_dense, iters=5)
+        sdpa_ms, sdpa_backend, sdpa_all = time_sdpa(q, k, v)
+        best = min(dense_ms, sdpa_ms) if sdpa_ms is not None else dense_ms
         out["attn"].update({"dense_same_kernel_ms": round(dense_ms, 3),
-                            "dense_torch_sdpa_ms": round(sdpa_ms, 3) if isinstance(sdpa_ms, float) else sdpa_ms,
+                            "dense_torch_sdpa_ms": round(sdpa_ms, 3) if sdpa_ms is not None else None,
+                            "dense_torch_sdpa_backend": sdpa_backend,
+                            "dense_torch_sdpa_backends_tried": {n: (round(t, 3) if isinstance(t, float) else t)
+                                                                for n, t in sdpa_all.items()},
                             "speedup_vs_fastest_dense": round(best / attn_ms, 3)})
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(wl, plan, q, k, v, dense_flops)
+        out["cpu_baseline"] = cpu_baseline(wl, plan, q, k, v, buf, dense_flops)
+        out["near_tie_rows"] = out["cpu_baseline"]["mask"].get("near_tie_rows")
     print(json.dumps(out))
 
 

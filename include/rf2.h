@@ -18,7 +18,10 @@
  *     Nothing throws, aborts or synchronises the device behind the caller's back.
  *   - Pointers named *_host are host memory; every other tensor pointer is DEVICE
  *     memory on the device that was current when the plan was created.  The
- *     caller owns all tensors; the plan owns only its index tables.
+ *     caller owns all tensors; the plan owns only its index tables.  A compute
+ *     call made while another device is current returns RF2_ERR_INVALID_ARG
+ *     (it would launch against the wrong device's tables); a plan created
+ *     without any device returns RF2_ERR_HIP from every compute call.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
  *     work is enqueued asynchronously on it.
  *   - Tensors are dense, contiguous, row-major in the stated shape.  "bf16" is the
@@ -80,7 +83,8 @@ typedef struct {
   int32_t batch, heads, head_dim; /* head_dim in {64, 128} */
   int32_t T, H, W;                /* latent grid (frames, height, width); T = 1 for an image */
   int32_t wt, wh, ww;             /* window of the Sec. 3.3 permutation; all three 0 = default:
-                                     b=128: video (2,8,8), image (1,8,16); b=64: video (4,4,4), image (1,8,8) */
+                                     b=256: video (4,8,8), image (1,16,16); b=128: video (2,8,8), image (1,8,16);
+                                     b=64: video (4,4,4), image (1,8,8) */
   int32_t block;                  /* b_q, rows of a Q block, in {64, 128, 256}; also b_k unless block_k is set */
   int32_t sink_frames;            /* leading frames treated as the Sec. 3.4 sink: 0 or more, < T */
   int32_t sink_at_end;            /* 1: sink tokens placed after the body (Sec. 3.4, last paragraph); 0: before */

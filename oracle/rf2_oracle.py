@@ -319,6 +319,25 @@ def block_sparse_attention(Qp: np.ndarray, Kp: np.ndarray, Vp: np.ndarray, M: np
 
 
 # --------------------------------------------------------------------------
+# diagnostic: how much of the dense attention the block mask keeps
+# --------------------------------------------------------------------------
+def attention_mass_recall(Qp: np.ndarray, Kp: np.ndarray, M: np.ndarray, b: int, bk: int | None = None,
+                          queries=None) -> float:
+    """Mean, over the query rows `queries` of the permuted sequence (default: all), of the
+    probability mass that DENSE attention (softmax(q K^T / sqrt(d)) over every key, Sec. 3.1
+    first paragraph) puts on the keys of the K blocks the mask keeps for that query's Q block.
+    1 for a mask of ones; the kept share of keys when all logits are equal."""
+    N, d = Qp.shape
+    bk = b if bk is None else bk
+    rows = np.arange(N) if queries is None else np.asarray(queries)
+    z = (Qp[rows] @ Kp.T) / math.sqrt(d)
+    p = np.exp(z - z.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    kept = M[rows // b][:, np.arange(N) // bk]            # [queries, keys]: is the key's block kept for this query
+    return float((p * kept).sum(axis=1).mean())
+
+
+# --------------------------------------------------------------------------
 # whole layer for one head
 # --------------------------------------------------------------------------
 def layer(Q: np.ndarray, K: np.ndarray, V: np.ndarray, *, T: int, H: int, W: int, block: int,
