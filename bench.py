@@ -54,6 +54,74 @@ def measured_traffic(workload: str):
     return None
 
 
+class PowerSampler:
+    """Socket power from the amdgpu hwmon files (microwatts), sampled by a thread every 20 ms; None where
+    the files are missing or unreadable.  Samples of the first `skip_s` seconds are dropped (the power
+    management needs a moment to settle on a kernel's own level)."""
+
+    def __init__(self, skip_s=0.0):
+        import glob
+        self.files = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        self.cap = None
+        for f in self.files[:1]:
+            try:
+                self.cap = int(open(f.replace("power1_input", "power1_cap")).read()) * 1e-6
+            except (OSError, ValueError):
+                pass
+        self.skip_s, self.samples, self._stop, self._thread = skip_s, [], False, None
+
+    def _run(self):
+        t0 = time.perf_counter()
+        while not self._stop:
+            try:
+                w = int(open(self.files[0]).read()) * 1e-6
+                if time.perf_counter() - t0 >= self.skip_s:
+                    self.samples.append(w)
+            except (OSError, ValueError):
+                return
+            time.sleep(0.02)
+
+    def __enter__(self):
+        if self.files:
+            import threading
+            self._thread = threading.Thread(target=self._run, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        if self._thread:
+            self._thread.join()
+
+    def mean(self):
+        return round(sum(self.samples) / len(self.samples), 1) if self.samples else None
+
+
+def power_report(plan, buf):
+    """What the chip draws and sustains: the attention kernel looped for ~1.5 s, and a loop of nothing but
+    bf16 MFMAs on pseudo-random operands for as long, each with the socket power sampled beside it."""
+    call = lambda: plan.rf2_block_sparse_attn_unpermuted(buf["qp"], buf["kp"], buf["vp"], buf["blk_idx"],
+                                                         buf["blk_cnt"], buf["o"])
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(); call(); b.record(); torch.cuda.synchronize()
+    one = max(a.elapsed_time(b), 0.05)
+    n_warm, n_timed = max(2, int(500 / one)), max(3, int(1000 / one))
+    with PowerSampler(skip_s=0.5) as ps:
+        for _ in range(n_warm):
+            call()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n_timed):
+            call()
+        b.record()
+        torch.cuda.synchronize()
+    attn_ms, attn_w, cap = a.elapsed_time(b) / n_timed, ps.mean(), ps.cap
+    with PowerSampler(skip_s=0.5) as ps:
+        sustained = rf2.rf2_measure_sustained_mfma(1.5)
+    return {"power_cap_w": cap, "attn_steady_ms": round(attn_ms, 4), "attn_power_w": attn_w,
+            "mfma_random_operands_sustained_tflops": round(sustained, 1), "mfma_random_operands_power_w": ps.mean()}
+
+
 def ensure_library():
     if not os.path.exists(rf2.LIB_PATH):
         from paper_2512_24086_amd.build import build
@@ -221,6 +289,7 @@ def main():
                     help="cumulative-mass block selection with this threshold instead of top-n (row lengths vary)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention baselines")
+    ap.add_argument("--no-power", action="store_true", help="skip the power / sustained-MFMA measurement (~3 s)")
     ap.add_argument("--unfused", action="store_true",
                     help="time rf2_block_sparse_attn + rf2_unpermute instead of the fused entry point")
     args = ap.parse_args()
@@ -297,6 +366,12 @@ def main():
                                  if args.sparsity is None and not wl.text_tokens and args.cdf is None
                                  and not args.head_dim and not args.block and not args.block_k else None)},
     }
+    if not args.no_power:
+        pw = power_report(plan, buf)
+        steady_tflops = kept_flops / (pw["attn_steady_ms"] * 1e-3) / 1e12
+        pw["attn_steady_kept_tflops"] = round(steady_tflops, 1)
+        pw["attn_frac_of_sustained_mfma"] = round(steady_tflops / pw["mfma_random_operands_sustained_tflops"], 4)
+        out["power"] = pw
     if not args.no_dense:
         cnt_dense = torch.full_like(buf["blk_cnt"], i.n_blocks_k)
         dense_ms = time_attn_only(plan, buf, buf["blk_idx"], cnt_dense, iters=5)

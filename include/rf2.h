@@ -244,6 +244,27 @@ int rf2_unpermute(const rf2_plan* plan, const void* op, void* o, void* stream);
  */
 int rf2_measure_peaks(double* mfma_bf16_tflops, double* copy_gbps, void* stream);
 
+/*
+ * Measurement aid: the bf16 MFMA rate the device SUSTAINS for `seconds` (0 < seconds <= 30) of a loop of
+ * nothing but v_mfma_f32_32x32x16_bf16 on pseudo-random operands.  The matrix cores draw much more power
+ * on varying data than on the constant operands of rf2_measure_peaks, and a loop of this length runs at
+ * the clock the power limit allows; this is the ceiling a kernel made of real products can approach.
+ * The first third of the time is warm-up, the rate is taken over the rest.
+ *   mfma_bf16_tflops : TFLOP/s (host, out)
+ * Allocates and frees a few bytes of device memory; synchronises with `stream`.
+ */
+int rf2_measure_sustained_mfma(double seconds, double* mfma_bf16_tflops, void* stream);
+
+/*
+ * Measurement aid: does workgroup g of a one-dimensional grid run on XCD g % 8?  The attention kernel's
+ * work order relies on it (each XCD has its own L2; a contiguous range of a head's Q blocks is given to
+ * one XCD).  Launches 8192 workgroups that read the hardware's XCC_ID register.
+ *   n_agree      : workgroups whose XCD number equals g % 8 (host, out)
+ *   n_workgroups : workgroups launched (host, out)
+ * Allocates and frees 32 KiB of device memory; synchronises with `stream`.
+ */
+int rf2_probe_xcd_mapping(int32_t* n_agree, int32_t* n_workgroups, void* stream);
+
 /* Static description of an error code; for RF2_ERR_HIP the text of the last HIP error seen
  * by the calling thread is appended. */
 const char* rf2_strerror(int code);

@@ -24,6 +24,44 @@ __global__ void __launch_bounds__(256) mfma_loop_kernel(float* sink, int iters) 
   if (s == 12345.f) sink[0] = s;   // never true: keeps the loop alive
 }
 
+// The same loop on operands that differ from lane to lane and from register to register (pseudo-random
+// bf16 values in (-2, 2)): the matrix cores draw far more power on such data than on constants, and what
+// the chip sustains under its power limit is this rate, not the one of the loop above.
+__global__ void __launch_bounds__(256) mfma_random_loop_kernel(float* sink, int iters) {
+  uint32_t seed = threadIdx.x * 7919u + blockIdx.x * 104729u + 1u;
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      seed = seed * 1664525u + 1013904223u;
+      a[i][e] = (__bf16)(((int)(seed >> 8) - (1 << 23)) * (1.0f / (1 << 22)));
+      seed = seed * 1664525u + 1013904223u;
+      b[i][e] = (__bf16)(((int)(seed >> 8) - (1 << 23)) * (1.0f / (1 << 22)));
+    }
+  f32x16 c0 = {}, c1 = {}, c2 = {}, c3 = {};
+  for (int it = 0; it < iters; ++it) {
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[2], c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[3], b[3], c3, 0, 0, 0);
+    if ((it & 63) == 63) {   // keep the accumulators in range
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { c0[i] *= 1e-3f; c1[i] *= 1e-3f; c2[i] *= 1e-3f; c3[i] *= 1e-3f; }
+    }
+  }
+  const float s = c0[0] + c1[1] + c2[2] + c3[3];
+  if (s == 12345.f) sink[0] = s;   // never true: keeps the loop alive
+}
+
+// Workgroup g of a one-dimensional grid records the number of the XCD (accelerator die) it runs on.
+__global__ void __launch_bounds__(256) xcd_of_workgroup_kernel(int32_t* out) {
+  const int xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));   // hardware register XCC_ID, bits 3:0
+  float x = (float)threadIdx.x;
+  for (int i = 0; i < 2000; ++i) x = x * 1.0001f + 0.5f;    // stay resident for a while, so that the grid spreads out
+  if (threadIdx.x == 0) out[blockIdx.x] = xcc + (x == 12345.f ? 1 : 0);
+}
+
 __global__ void __launch_bounds__(256) copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n; i += stride) dst[i] = src[i];
@@ -77,4 +115,62 @@ extern "C" int rf2_measure_peaks(double* mfma_bf16_tflops, double* copy_gbps, vo
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
   return rc;
+}
+
+extern "C" int rf2_measure_sustained_mfma(double seconds, double* mfma_bf16_tflops, void* stream) {
+  if (!mfma_bf16_tflops || !(seconds > 0.0) || seconds > 30.0) return RF2_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  int dev = 0, n_cu = 0;
+  RF2_HIP(hipGetDevice(&dev));
+  RF2_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+  float* sink = nullptr;
+  hipEvent_t e0, e1;
+  RF2_HIP(hipMalloc((void**)&sink, 256));
+  hipError_t e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  if (e != hipSuccess) { (void)hipFree(sink); return rf2_note_hip_error(e); }
+  const int iters = 20000, wgs = 2 * n_cu;
+  const double flop_per_launch = (double)wgs * 4 /*wavefronts*/ * iters * 4 /*MFMAs*/ * 2.0 * 32 * 32 * 16;
+  double total_ms = 0.0, timed_ms = 0.0;
+  long launches = 0;
+  // the first third of the time only warms up (the clock settles at the power limit), the rest is timed
+  while (e == hipSuccess && total_ms < seconds * 1e3) {
+    float ms = 0.f;
+    e = hipEventRecord(e0, st);
+    for (int r = 0; r < 4 && e == hipSuccess; ++r) {
+      mfma_random_loop_kernel<<<wgs, 256, 0, st>>>(sink, iters);
+      e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (total_ms >= seconds * 1e3 / 3.0) { timed_ms += ms; launches += 4; }
+    total_ms += ms;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  (void)hipFree(sink);
+  if (e != hipSuccess) return rf2_note_hip_error(e);
+  *mfma_bf16_tflops = launches ? flop_per_launch * (double)launches / (timed_ms * 1e-3) / 1e12 : 0.0;
+  return RF2_OK;
+}
+
+extern "C" int rf2_probe_xcd_mapping(int32_t* n_agree, int32_t* n_workgroups, void* stream) {
+  if (!n_agree || !n_workgroups) return RF2_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const int n = 8192;
+  int32_t* d = nullptr;
+  RF2_HIP(hipMalloc((void**)&d, n * sizeof(int32_t)));
+  std::vector<int32_t> h((size_t)n, -1);
+  xcd_of_workgroup_kernel<<<n, 256, 0, st>>>(d);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) e = hipMemcpyAsync(h.data(), d, n * sizeof(int32_t), hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  (void)hipFree(d);
+  if (e != hipSuccess) return rf2_note_hip_error(e);
+  int agree = 0;
+  for (int g = 0; g < n; ++g) agree += (h[(size_t)g] == (g & 7));
+  *n_agree = agree;
+  *n_workgroups = n;
+  return RF2_OK;
 }

@@ -49,6 +49,8 @@ SIGNATURES = {
     "rf2_block_sparse_attn_unpermuted": (C.c_int, [C.c_void_p] * 9),
     "rf2_unpermute": (C.c_int, [C.c_void_p] * 4),
     "rf2_measure_peaks": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
+    "rf2_measure_sustained_mfma": (C.c_int, [C.c_double, C.POINTER(C.c_double), C.c_void_p]),
+    "rf2_probe_xcd_mapping": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]),
     "rf2_strerror": (C.c_char_p, [C.c_int]),
     "rf2_version": (C.c_int, []),
 }
@@ -99,6 +101,21 @@ def rf2_measure_peaks(stream=None):
     mfma, copy = C.c_double(0.0), C.c_double(0.0)
     _check(lib().rf2_measure_peaks(C.byref(mfma), C.byref(copy), _stream(stream)), "rf2_measure_peaks")
     return mfma.value, copy.value
+
+
+def rf2_measure_sustained_mfma(seconds, stream=None):
+    """bf16 MFMA TFLOP/s sustained for `seconds` on pseudo-random operands (the power-limited ceiling)."""
+    out = C.c_double(0.0)
+    _check(lib().rf2_measure_sustained_mfma(C.c_double(seconds), C.byref(out), _stream(stream)),
+           "rf2_measure_sustained_mfma")
+    return out.value
+
+
+def rf2_probe_xcd_mapping(stream=None):
+    """(workgroups found on XCD blockIdx % 8, workgroups launched)."""
+    agree, total = C.c_int32(0), C.c_int32(0)
+    _check(lib().rf2_probe_xcd_mapping(C.byref(agree), C.byref(total), _stream(stream)), "rf2_probe_xcd_mapping")
+    return agree.value, total.value
 
 
 class Plan:

@@ -396,3 +396,19 @@ def test_measured_peaks_are_plausible():
     mfma, copy = rf2.rf2_measure_peaks()
     assert 500.0 < mfma <= 2600.0, mfma        # dense bf16 peak of the chip is 2.5 PFLOP/s
     assert 1000.0 < copy <= 8200.0, copy       # HBM3E peak is 8 TB/s
+
+
+def test_workgroups_land_on_the_xcd_the_work_order_assumes():
+    """The attention kernel gives XCD g % 8 the workgroups g of a launch (its tables hand each XCD a
+    contiguous range of a head's Q blocks, so that their K/V tiles meet in one L2)."""
+    from paper_2512_24086_amd import rf2
+    agree, total = rf2.rf2_probe_xcd_mapping()
+    assert total == 8192 and agree == total, (agree, total)
+
+
+def test_sustained_mfma_rate_is_below_the_short_loop():
+    """Pseudo-random operands under the power limit: a plausible rate, and not above the constant-operand loop."""
+    from paper_2512_24086_amd import rf2
+    short, _ = rf2.rf2_measure_peaks()
+    sustained = rf2.rf2_measure_sustained_mfma(0.6)
+    assert 300.0 < sustained <= short * 1.02, (sustained, short)
