@@ -256,14 +256,19 @@ int rf2_measure_peaks(double* mfma_bf16_tflops, double* copy_gbps, void* stream)
 int rf2_measure_sustained_mfma(double seconds, double* mfma_bf16_tflops, void* stream);
 
 /*
- * Measurement aid: does workgroup g of a one-dimensional grid run on XCD g % 8?  The attention kernel's
- * work order relies on it (each XCD has its own L2; a contiguous range of a head's Q blocks is given to
- * one XCD).  Launches 8192 workgroups that read the hardware's XCC_ID register.
- *   n_agree      : workgroups whose XCD number equals g % 8 (host, out)
- *   n_workgroups : workgroups launched (host, out)
+ * Measurement aid: do the workgroups g of a one-dimensional grid with equal g % 8 share an XCD, and do
+ * the eight residue classes sit on eight different XCDs?  The attention kernel's work order relies on
+ * exactly that (each XCD has its own L2; the Q blocks handed to the workgroups of one class are a
+ * contiguous range of a head).  Which XCD a class lands on is NOT fixed: the hardware continues its
+ * round-robin where the previous launch stopped, so workgroup 0 may start on any XCD.  Launches 8192
+ * workgroups that read the hardware's XCC_ID register.
+ *   n_agree      : workgroups that run on the XCD of their class, the classes being on 8 different XCDs
+ *                  (0 if they are not)                                               (host, out)
+ *   n_workgroups : workgroups launched                                              (host, out)
+ *   first_xcd    : XCD of workgroup 0, may be NULL                                  (host, out)
  * Allocates and frees 32 KiB of device memory; synchronises with `stream`.
  */
-int rf2_probe_xcd_mapping(int32_t* n_agree, int32_t* n_workgroups, void* stream);
+int rf2_probe_xcd_mapping(int32_t* n_agree, int32_t* n_workgroups, int32_t* first_xcd, void* stream);
 
 /* Static description of an error code; for RF2_ERR_HIP the text of the last HIP error seen
  * by the calling thread is appended. */

@@ -151,6 +151,7 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
   // Slots of an XCD, in issue order: the all-column sink rows of every head first, then the ordinary
   // rows head by head.  A sink row is several times longer than an ordinary one; issued first (longest
   // jobs first) none of them is left running alone at the end, and the short rows fill the tail evenly.
+  // (workgroups with equal blockIdx % 8 share an XCD; which of the eight it is varies from launch to launch)
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   int bh, entry;
   if (slot < n_bh * sink_per_xcd) {

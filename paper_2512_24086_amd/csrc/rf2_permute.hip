@@ -68,12 +68,13 @@ __global__ void __launch_bounds__(256) permute_pool_kernel(
 // Position inside a 16-key group of the key-major V tile -> key offset (see rf2.h).
 __device__ __forceinline__ int rho(int r) { return (r & 3) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
-// One workgroup gathers one block of BLK permuted rows of V into LDS and writes the
-// block as BLK/64 operand parts [8][D][8] of the attention kernel's second product.
+// One workgroup gathers the 64 permuted rows of V that make up one operand part into LDS and writes
+// the part [8][D][8] of the attention kernel's second product (16 KiB or 8 KiB, contiguous).
 // Storage position s of a key inside its block: each 16-key group is listed in the order
 // 0-3, 8-11, 4-7, 12-15.  With KH = BLK/2, position s goes to part (s % KH) / 32, chunk
 // g = (s / KH)*4 + (s % 32) / 8, element s % 8; the 16-byte chunk (part, g, ch) holds
-// channel ch of those 8 keys.
+// channel ch of those 8 keys.  A part thus holds the block rows 32*part .. 32*part+31 and
+// KH + 32*part .. KH + 32*part + 31 (the reordering stays inside a 16-key group).
 template <int D, int BLK>
 __global__ void __launch_bounds__(256) permute_vtile_kernel(
     const uint4* __restrict__ v, uint4* __restrict__ vp, const int32_t* __restrict__ perm, int N, int n_blocks,
@@ -81,25 +82,25 @@ __global__ void __launch_bounds__(256) permute_vtile_kernel(
   constexpr int CH = D / 8;
   constexpr int RG = 256 / CH;
   constexpr int PITCH = D + 2;       // u16 elements per LDS row: odd number of dwords
-  __shared__ __attribute__((aligned(16))) u16 tile[BLK * PITCH];
-  const int blk = blockIdx.x, bh = blockIdx.y;
+  constexpr int PB = BLK / 64, KH = BLK / 2;
+  __shared__ __attribute__((aligned(16))) u16 tile[64 * PITCH];
+  const int blk = blockIdx.x / PB, part = blockIdx.x % PB, bh = blockIdx.y;
   const uint4* __restrict__ src = v + ((bh / heads) * st.batch + (bh % heads) * st.head) * CH;
   const int c = threadIdx.x % CH, rg = threadIdx.x / CH;
-  for (int r = rg; r < BLK; r += RG) {
+#pragma unroll
+  for (int lr = rg; lr < 64; lr += RG) {                      // local row -> block row
+    const int r = (lr / 32) * KH + part * 32 + lr % 32;
     const int n = perm[blk * BLK + r];
     uint4 x = make_uint4(0u, 0u, 0u, 0u);
     if (n >= 0) x = src[(size_t)n * st.token * CH + c];
-    uint32_t* row = reinterpret_cast<uint32_t*>(tile + r * PITCH + c * 8);  // 4-byte aligned: PITCH, c*8 even
+    uint32_t* row = reinterpret_cast<uint32_t*>(tile + lr * PITCH + c * 8);  // 4-byte aligned: PITCH, c*8 even
     row[0] = x.x; row[1] = x.y; row[2] = x.z; row[3] = x.w;
   }
   __syncthreads();
-  constexpr int OC = BLK / 8;        // key chunks per block
-  constexpr int KH = BLK / 2;
-  uint4* __restrict__ dst = vp + ((size_t)bh * n_blocks + blk) * D * OC;
-  for (int o = threadIdx.x; o < D * OC; o += 256) {
-    const int pg = o / D, ch = o % D;  // consecutive lanes -> consecutive channels: contiguous 16-byte stores
-    const int part = pg / 8, g = pg % 8;
-    const int sbase = (g / 4) * KH + part * 32 + (g % 4) * 8;   // first storage position of this chunk
+  uint4* __restrict__ dst = vp + (((size_t)bh * n_blocks + blk) * PB + part) * D * 8;
+  for (int o = threadIdx.x; o < D * 8; o += 256) {
+    const int g = o / D, ch = o % D;   // consecutive lanes -> consecutive channels: contiguous 16-byte stores
+    const int sbase = (g / 4) * 32 + (g % 4) * 8;             // first local storage position of this chunk
     uint32_t w[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -151,8 +152,9 @@ void launch_permute_kv(const rf2_plan* plan, const void* k, const void* v, void*
   permute_pool_kernel<D, BK, true><<<grid, 256, 0, st>>>((const uint4*)k, (uint4*)kp, kbar, plan->d_perm, (int)in.N,
                                                           in.n_blocks_k, in.last_block_valid_k, plan->cfg.heads,
                                                           rf2_qkv_strides(plan));
-  permute_vtile_kernel<D, BK><<<grid, 256, 0, st>>>((const uint4*)v, (uint4*)vp, plan->d_perm, (int)in.N,
-                                                     in.n_blocks_k, plan->cfg.heads, rf2_qkv_strides(plan));
+  const dim3 grid_v(in.n_blocks_k * (BK / 64), plan->cfg.batch * plan->cfg.heads, 1);   // one workgroup per 64-key part
+  permute_vtile_kernel<D, BK><<<grid_v, 256, 0, st>>>((const uint4*)v, (uint4*)vp, plan->d_perm, (int)in.N,
+                                                       in.n_blocks_k, plan->cfg.heads, rf2_qkv_strides(plan));
 }
 
 template <int D>

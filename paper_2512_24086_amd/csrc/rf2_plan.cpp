@@ -178,7 +178,7 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
       }
   for (int64_t n = n_video; n < N; ++n) p->inv[(size_t)n] = p->perm[(size_t)n] = (int32_t)n;   // text: in place, last
 
-  // Work tables of the attention kernel.  Workgroup g runs on XCD g % 8.  A head's all-column
+  // Work tables of the attention kernel.  Workgroups g with equal g % 8 run on one XCD.  A head's all-column
   // sink rows are dealt round-robin to the XCDs; each XCD also gets a contiguous range of the
   // head's ordinary Q blocks (neighbouring blocks tend to pick the same K blocks, so they share
   // its L2).  The kernel decides the issue order of the two kinds (sink rows run ahead).

@@ -155,7 +155,7 @@ extern "C" int rf2_measure_sustained_mfma(double seconds, double* mfma_bf16_tflo
   return RF2_OK;
 }
 
-extern "C" int rf2_probe_xcd_mapping(int32_t* n_agree, int32_t* n_workgroups, void* stream) {
+extern "C" int rf2_probe_xcd_mapping(int32_t* n_agree, int32_t* n_workgroups, int32_t* first_xcd, void* stream) {
   if (!n_agree || !n_workgroups) return RF2_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
   const int n = 8192;
@@ -168,9 +168,15 @@ extern "C" int rf2_probe_xcd_mapping(int32_t* n_agree, int32_t* n_workgroups, vo
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   (void)hipFree(d);
   if (e != hipSuccess) return rf2_note_hip_error(e);
+  // the first eight workgroups define where each residue class g % 8 lives; the classes must sit on
+  // eight different XCDs and every later workgroup on the XCD of its class
+  bool distinct = true;
+  for (int a = 0; a < 8; ++a)
+    for (int b = a + 1; b < 8; ++b) distinct = distinct && h[(size_t)a] != h[(size_t)b];
   int agree = 0;
-  for (int g = 0; g < n; ++g) agree += (h[(size_t)g] == (g & 7));
+  for (int g = 0; g < n; ++g) agree += (distinct && h[(size_t)g] == h[(size_t)(g & 7)]);
   *n_agree = agree;
   *n_workgroups = n;
+  if (first_xcd) *first_xcd = h[0];
   return RF2_OK;
 }

@@ -50,7 +50,7 @@ SIGNATURES = {
     "rf2_unpermute": (C.c_int, [C.c_void_p] * 4),
     "rf2_measure_peaks": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
     "rf2_measure_sustained_mfma": (C.c_int, [C.c_double, C.POINTER(C.c_double), C.c_void_p]),
-    "rf2_probe_xcd_mapping": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]),
+    "rf2_probe_xcd_mapping": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]),
     "rf2_strerror": (C.c_char_p, [C.c_int]),
     "rf2_version": (C.c_int, []),
 }
@@ -112,10 +112,11 @@ def rf2_measure_sustained_mfma(seconds, stream=None):
 
 
 def rf2_probe_xcd_mapping(stream=None):
-    """(workgroups found on XCD blockIdx % 8, workgroups launched)."""
-    agree, total = C.c_int32(0), C.c_int32(0)
-    _check(lib().rf2_probe_xcd_mapping(C.byref(agree), C.byref(total), _stream(stream)), "rf2_probe_xcd_mapping")
-    return agree.value, total.value
+    """(workgroups on the XCD of their residue class g % 8, workgroups launched, XCD of workgroup 0)."""
+    agree, total, first = C.c_int32(0), C.c_int32(0), C.c_int32(-1)
+    _check(lib().rf2_probe_xcd_mapping(C.byref(agree), C.byref(total), C.byref(first), _stream(stream)),
+           "rf2_probe_xcd_mapping")
+    return agree.value, total.value, first.value
 
 
 class Plan:
