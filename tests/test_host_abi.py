@@ -66,6 +66,11 @@ def test_null_arguments_are_rejected():
     assert lib.rf2_block_sparse_attn(*([None] * 9)) == rf2.RF2_ERR_INVALID_ARG
     assert lib.rf2_unpermute(*([None] * 4)) == rf2.RF2_ERR_INVALID_ARG
     assert lib.rf2_measure_peaks(None, None, None) == rf2.RF2_ERR_INVALID_ARG
+    out = C.c_double(0.0)
+    assert lib.rf2_measure_sustained_mfma(C.c_double(1.0), None, None) == rf2.RF2_ERR_INVALID_ARG
+    for bad_seconds in (0.0, -1.0, float("nan"), 31.0):
+        assert lib.rf2_measure_sustained_mfma(C.c_double(bad_seconds), C.byref(out), None) == rf2.RF2_ERR_INVALID_ARG
+    assert lib.rf2_probe_xcd_mapping(None, None, None, None) == rf2.RF2_ERR_INVALID_ARG
     assert lib.rf2_plan_destroy(None) == rf2.RF2_OK
 
 
@@ -172,3 +177,26 @@ def test_equal_blocks_report_the_same_k_side():
     assert (i.block_k, i.n_blocks_k, i.N_pad_k, i.last_block_valid_k) == (64, i.n_blocks, i.N_pad, i.last_block_valid)
     assert (i.sink_block_begin_k, i.sink_block_end_k) == (i.sink_block_begin, i.sink_block_end)
     p.close()
+
+
+def test_bench_reports_traffic_only_for_the_kernel_source_it_was_measured_on(tmp_path, monkeypatch):
+    """bench.py's roofline.traffic comes from a table keyed by the hash of the attention kernel's source;
+    a figure measured on another version of the kernel must not be reported."""
+    import sys
+    sys.path.insert(0, ROOT)
+    import bench
+    here = bench.attn_source_hash()
+    assert len(here) == 16 and int(here, 16) >= 0
+    table = tmp_path / "attn_traffic.txt"
+    table.write_text(f"# comment\nvideo720p 0000000000000000 9.9e11 stale\nvideo720p {here} 1.5e11 current\nimage {here} 7e8 x\n")
+    monkeypatch.setattr(bench, "TRAFFIC_TABLE", str(table))
+    assert bench.measured_traffic("video720p") == 1.5e11
+    assert bench.measured_traffic("image") == 7e8
+    assert bench.measured_traffic("video480p") is None
+    table.write_text("video720p 0000000000000000 9.9e11 stale\n")
+    assert bench.measured_traffic("video720p") is None
+    monkeypatch.setattr(bench, "TRAFFIC_TABLE", str(tmp_path / "missing.txt"))
+    assert bench.measured_traffic("video720p") is None
+    # the table in the tree has an entry for the source in the tree
+    monkeypatch.undo()
+    assert bench.measured_traffic("video720p") is not None, "profiles/attn_traffic.txt is stale: re-measure FETCH_SIZE / WRITE_SIZE"
