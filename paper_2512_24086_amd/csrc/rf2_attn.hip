@@ -192,13 +192,14 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
   // re-fetch the last part into a free slot, which keeps the outstanding-load count uniform).
   // A list entry is read one odd step before it is needed (list_entry) and turned into an offset
   // only when it is used (part_off), so that no step waits for a scalar memory load.
+  // (part numbers are never negative: unsigned division and remainder are a shift and a mask)
   auto list_entry = [&](int P) {
-    const int it = min(P, NPARTS - 1) / C::PB;
+    const int it = (int)((unsigned)min(P, NPARTS - 1) / (unsigned)C::PB);
     return dense ? it : list[it];
   };
   auto part_off = [&](int entry, int P) {
     const int j = min(max(entry, 0), Tb - 1);            // a corrupt list can give wrong results, never a fault
-    return (uint32_t)j * (uint32_t)C::TILE_BYTES + (uint32_t)(min(P, NPARTS - 1) % C::PB) * (uint32_t)C::PART_BYTES;
+    return (uint32_t)j * (uint32_t)C::TILE_BYTES + ((unsigned)min(P, NPARTS - 1) % (unsigned)C::PB) * (uint32_t)C::PART_BYTES;
   };
   auto part_at = [&](int P) { return (size_t)part_off(list_entry(P), P); };
   const uint32_t ring_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)ring;
