@@ -52,7 +52,8 @@ enum {
   RF2_ERR_INVALID_ARG = -1, /* NULL where not allowed, size out of range, inconsistent config */
   RF2_ERR_UNSUPPORTED = -2, /* head_dim or block size this build has no kernel for */
   RF2_ERR_ALLOC = -3,       /* host or device allocation of the plan's tables failed */
-  RF2_ERR_HIP = -4          /* a HIP runtime call or kernel launch reported an error */
+  RF2_ERR_HIP = -4,         /* a HIP runtime call or kernel launch reported an error */
+  RF2_ERR_TOO_LARGE = -5    /* a size beyond the fixed capacity of the library's static device array */
 };
 
 /* How `sparsity` becomes a per-row block count (the paper only names a sparsity level). */
@@ -269,6 +270,26 @@ int rf2_measure_sustained_mfma(double seconds, double* mfma_bf16_tflops, void* s
  * Allocates and frees 32 KiB of device memory; synchronises with `stream`.
  */
 int rf2_probe_xcd_mapping(int32_t* n_agree, int32_t* n_workgroups, int32_t* first_xcd, void* stream);
+
+/*
+ * rf2_probe_xcd_mapping for callers that cannot allocate: code between other work of a serving loop,
+ * harnesses that forbid hipMalloc, callers that must not block.  Same probe kernel, same count; the
+ * per-workgroup table lives in a static device array of the library (32 KiB on every GPU the library
+ * runs on, held until the process ends), the count is taken by a second kernel, and the answer is left
+ * in device memory.  Calls no hipMalloc / hipFree and no other allocating routine, copies nothing to
+ * the host and does not synchronise: three kernel launches on `stream`.
+ *   n_launch : workgroups to launch, 8 <= n_launch <= RF2_XCD_PROBE_MAX_WORKGROUPS; fewer than 8:
+ *              RF2_ERR_INVALID_ARG; more: RF2_ERR_TOO_LARGE (nothing is launched)
+ *   result   : [2] int32 (device, out): result[0] = workgroups g < n_launch that ran on the XCD of
+ *              workgroup g % 8, the first eight being on eight different XCDs (0 if they are not),
+ *              i.e. rf2_probe_xcd_mapping's n_agree for n_launch workgroups; result[1] = XCD of
+ *              workgroup 0.  Valid once the work on `stream` has completed.
+ * The first call on a device looks the array's address up (hipGetSymbolAddress); every call on a GPU
+ * shares that GPU's array, which keeps the previous call's contents (the entries a call reads are
+ * reset by the call itself): calls that overlap on one GPU, on different streams, race.
+ */
+#define RF2_XCD_PROBE_MAX_WORKGROUPS 8192
+int rf2_probe_xcd_mapping_static(int32_t n_launch, int32_t* result, void* stream);
 
 /* Static description of an error code; for RF2_ERR_HIP the text of the last HIP error seen
  * by the calling thread is appended. */

@@ -64,6 +64,7 @@ const char* rf2_strerror(int code) {
     case RF2_ERR_INVALID_ARG: return "invalid argument";
     case RF2_ERR_UNSUPPORTED: return "unsupported head_dim / block size / problem size";
     case RF2_ERR_ALLOC: return "allocation failed";
+    case RF2_ERR_TOO_LARGE: return "size exceeds the capacity of the library's static device array";
     case RF2_ERR_HIP:
       g_strerror_buf = "HIP error: " + g_hip_error_text;
       return g_strerror_buf.c_str();

@@ -3,6 +3,14 @@
 // bandwidth of a plain device-to-device copy kernel.
 #include "rf2_internal.h"
 
+#include <mutex>
+
+// Per-workgroup table of rf2_probe_xcd_mapping_static: 32 KiB on every GPU the library runs on, held
+// until the process ends.  In host code this name is only a handle for hipGetSymbolAddress: the
+// array's address on a device is looked up once per device (scratch_on_current_device) and it is
+// that pointer which kernels and copies receive.
+static __device__ __align__(256) int32_t scratch[RF2_XCD_PROBE_MAX_WORKGROUPS];
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -60,6 +68,53 @@ __global__ void __launch_bounds__(256) xcd_of_workgroup_kernel(int32_t* out) {
   float x = (float)threadIdx.x;
   for (int i = 0; i < 2000; ++i) x = x * 1.0001f + 0.5f;    // stay resident for a while, so that the grid spreads out
   if (threadIdx.x == 0) out[blockIdx.x] = xcc + (x == 12345.f ? 1 : 0);
+}
+
+__global__ void __launch_bounds__(256) fill_kernel(int32_t* p, int n, int32_t value) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = value;
+}
+
+// One workgroup: result[0] = entries g < n of the table that equal entry g % 8, provided the first
+// eight entries are eight different valid XCD numbers (0 otherwise); result[1] = entry 0.
+__global__ void __launch_bounds__(256) xcd_agreement_kernel(const int32_t* __restrict__ table, int n,
+                                                            int32_t* __restrict__ result) {
+  __shared__ int count;
+  if (threadIdx.x == 0) count = 0;
+  __syncthreads();
+  bool distinct = true;
+  for (int a = 0; a < 8; ++a) {
+    distinct = distinct && table[a] >= 0;
+    for (int b = a + 1; b < 8; ++b) distinct = distinct && table[a] != table[b];
+  }
+  int mine = 0;
+  for (int g = threadIdx.x; g < n; g += 256) mine += (distinct && table[g] == table[g & 7]);
+  atomicAdd(&count, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    result[0] = count;
+    result[1] = table[0];
+  }
+}
+
+// Address of `scratch` on the device that is current, looked up on the first call made on that device.
+std::mutex g_scratch_mutex;
+constexpr int MAX_DEVICES = 64;
+int32_t* g_scratch_ptr[MAX_DEVICES] = {};
+
+int scratch_on_current_device(int32_t** out) {
+  int dev = -1;
+  RF2_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return RF2_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    RF2_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return rf2_note_hip_error(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return RF2_OK;
 }
 
 __global__ void __launch_bounds__(256) copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
@@ -178,5 +233,22 @@ extern "C" int rf2_probe_xcd_mapping(int32_t* n_agree, int32_t* n_workgroups, in
   *n_agree = agree;
   *n_workgroups = n;
   if (first_xcd) *first_xcd = h[0];
+  return RF2_OK;
+}
+
+extern "C" int rf2_probe_xcd_mapping_static(int32_t n_launch, int32_t* result, void* stream) {
+  if (!result || n_launch < 8) return RF2_ERR_INVALID_ARG;
+  if (n_launch > RF2_XCD_PROBE_MAX_WORKGROUPS) return RF2_ERR_TOO_LARGE;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t* table = nullptr;
+  if (const int rc = scratch_on_current_device(&table)) return rc;
+  // the table keeps the previous call's entries: mark the ones this call reads, so that a workgroup
+  // that failed to report is counted as a disagreement and not as the last call's answer
+  fill_kernel<<<(n_launch + 255) / 256, 256, 0, st>>>(table, n_launch, -1);
+  RF2_LAUNCH_CHECK();
+  xcd_of_workgroup_kernel<<<n_launch, 256, 0, st>>>(table);
+  RF2_LAUNCH_CHECK();
+  xcd_agreement_kernel<<<1, 256, 0, st>>>(table, n_launch, result);
+  RF2_LAUNCH_CHECK();
   return RF2_OK;
 }

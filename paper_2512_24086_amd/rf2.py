@@ -14,7 +14,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "librf2.so")
 
 RF2_OK = 0
-RF2_ERR_INVALID_ARG, RF2_ERR_UNSUPPORTED, RF2_ERR_ALLOC, RF2_ERR_HIP = -1, -2, -3, -4
+RF2_ERR_INVALID_ARG, RF2_ERR_UNSUPPORTED, RF2_ERR_ALLOC, RF2_ERR_HIP, RF2_ERR_TOO_LARGE = -1, -2, -3, -4, -5
 RF2_BUDGET_GLOBAL, RF2_BUDGET_ROW_INCL_SINK, RF2_BUDGET_ROW_PLUS_SINK = 0, 1, 2
 RF2_LAYOUT_BHND, RF2_LAYOUT_BNHD = 0, 1
 RF2_SELECT_TOPN, RF2_SELECT_CDF = 0, 1
@@ -51,6 +51,7 @@ SIGNATURES = {
     "rf2_measure_peaks": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
     "rf2_measure_sustained_mfma": (C.c_int, [C.c_double, C.POINTER(C.c_double), C.c_void_p]),
     "rf2_probe_xcd_mapping": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]),
+    "rf2_probe_xcd_mapping_static": (C.c_int, [C.c_int32, C.c_void_p, C.c_void_p]),
     "rf2_strerror": (C.c_char_p, [C.c_int]),
     "rf2_version": (C.c_int, []),
 }
@@ -117,6 +118,12 @@ def rf2_probe_xcd_mapping(stream=None):
     _check(lib().rf2_probe_xcd_mapping(C.byref(agree), C.byref(total), C.byref(first), _stream(stream)),
            "rf2_probe_xcd_mapping")
     return agree.value, total.value, first.value
+
+
+def rf2_probe_xcd_mapping_static(n_launch, result, stream=None):
+    """Allocation-free probe: leaves (agreeing workgroups, XCD of workgroup 0) in `result` (device int32[2])."""
+    _check(lib().rf2_probe_xcd_mapping_static(C.c_int32(n_launch), _ptr(result), _stream(stream)),
+           "rf2_probe_xcd_mapping_static")
 
 
 class Plan:

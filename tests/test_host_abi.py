@@ -71,6 +71,12 @@ def test_null_arguments_are_rejected():
     for bad_seconds in (0.0, -1.0, float("nan"), 31.0):
         assert lib.rf2_measure_sustained_mfma(C.c_double(bad_seconds), C.byref(out), None) == rf2.RF2_ERR_INVALID_ARG
     assert lib.rf2_probe_xcd_mapping(None, None, None, None) == rf2.RF2_ERR_INVALID_ARG
+    # the allocation-free probe checks its sizes before it touches the device
+    dummy = C.c_void_p(0x1000)
+    assert lib.rf2_probe_xcd_mapping_static(C.c_int32(64), None, None) == rf2.RF2_ERR_INVALID_ARG
+    assert lib.rf2_probe_xcd_mapping_static(C.c_int32(7), dummy, None) == rf2.RF2_ERR_INVALID_ARG
+    assert lib.rf2_probe_xcd_mapping_static(C.c_int32(8193), dummy, None) == rf2.RF2_ERR_TOO_LARGE
+    assert b"static device array" in lib.rf2_strerror(rf2.RF2_ERR_TOO_LARGE)
     assert lib.rf2_plan_destroy(None) == rf2.RF2_OK
 
 
