@@ -7,6 +7,19 @@
 namespace {
 
 typedef unsigned short u16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+// Every row is read once and written once: non-temporal accesses keep the stream from displacing
+// other data in the caches on its way (measured on the 720p layer: loads alone -4 %, stores alone
+// +0.5 %, both -9 % of the time of the three kernels).
+__device__ __forceinline__ uint4 ld_stream(const uint4* p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st_stream(uint4* p, uint4 v) {
+  const u32x4 w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
+}
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -42,10 +55,10 @@ __global__ void __launch_bounds__(256) permute_pool_kernel(
   for (int r = rg; r < BLK; r += RG) {
     const int n = perm[blk * BLK + r];
     uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (n >= 0) v = src[(size_t)n * st.token * CH + c];
+    if (n >= 0) v = ld_stream(&src[(size_t)n * st.token * CH + c]);
     constexpr int KH = BLK / 2;
     const int kslot = ((r % KH) / 32 * CH + c) * 64 + (r / KH) * 32 + r % 32;
-    dst[IS_K ? kslot : r * CH + c] = v;
+    st_stream(&dst[IS_K ? kslot : r * CH + c], v);
     acc[0] += bf16_lo(v.x); acc[1] += bf16_hi(v.x);
     acc[2] += bf16_lo(v.y); acc[3] += bf16_hi(v.y);
     acc[4] += bf16_lo(v.z); acc[5] += bf16_hi(v.z);
@@ -92,7 +105,7 @@ __global__ void __launch_bounds__(256) permute_vtile_kernel(
     const int r = (lr / 32) * KH + part * 32 + lr % 32;
     const int n = perm[blk * BLK + r];
     uint4 x = make_uint4(0u, 0u, 0u, 0u);
-    if (n >= 0) x = src[(size_t)n * st.token * CH + c];
+    if (n >= 0) x = ld_stream(&src[(size_t)n * st.token * CH + c]);
     uint32_t* row = reinterpret_cast<uint32_t*>(tile + lr * PITCH + c * 8);  // 4-byte aligned: PITCH, c*8 even
     row[0] = x.x; row[1] = x.y; row[2] = x.z; row[3] = x.w;
   }
@@ -108,7 +121,7 @@ __global__ void __launch_bounds__(256) permute_vtile_kernel(
       const int k0 = (s0 & ~15) + rho(s0 & 15), k1 = (s1 & ~15) + rho(s1 & 15);
       w[e] = (uint32_t)tile[k0 * PITCH + ch] | ((uint32_t)tile[k1 * PITCH + ch] << 16);
     }
-    dst[o] = make_uint4(w[0], w[1], w[2], w[3]);
+    st_stream(&dst[o], make_uint4(w[0], w[1], w[2], w[3]));
   }
 }
 
@@ -127,7 +140,7 @@ __global__ void __launch_bounds__(256) unpermute_kernel(
 #pragma unroll 4
   for (int r = rg; r < 128; r += RG) {
     const int n = n0 + r;
-    if (n < N) dst[(size_t)n * st.token * CH + c] = src[(size_t)inv[n] * CH + c];
+    if (n < N) st_stream(&dst[(size_t)n * st.token * CH + c], ld_stream(&src[(size_t)inv[n] * CH + c]));
   }
 }
 
