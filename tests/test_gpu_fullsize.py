@@ -38,6 +38,15 @@ CASES = {
     "video720p_bnhd": ("video720p", 0.8, (29,)),
     "video720p_q128_k64": ("video720p", 0.8, (5,)),
     "video720p_q256_k64": ("video720p", 0.8, (36,)),
+    # the largest block counts a plan accepts (2,048 rows and columns of the block mask): the mask kernel's
+    # score strip at its full width (128 KiB of LDS), the longest lists, the largest work tables
+    "limit_2048_blocks_b128": ("limit_2048_blocks_b128", 0.9, (0, 1)),
+    "limit_2048_blocks_b64": ("limit_2048_blocks_b64", 0.9, (1,)),
+}
+# synthetic grids that exist only to reach the limits of the plan (not workloads of the paper)
+LIMIT_WORKLOADS = {
+    "limit_2048_blocks_b128": inputs.Workload("limit_2048_blocks_b128", 6, 1, 2, 64, 64, 64, 64, 128, 0.9, 1, 0.3),
+    "limit_2048_blocks_b64": inputs.Workload("limit_2048_blocks_b64", 7, 1, 2, 128, 32, 64, 64, 64, 0.9, 1, 0.3),
 }
 EXTRA = {"video720p_cdf_text": dict(cdf_threshold=0.9, text_tokens=512), "video720p_b64": dict(block=64),
          "video720p_q256_k128": dict(block=256, block_k=128), "video720p_d64": dict(head_dim=64),
@@ -59,7 +68,7 @@ class Big:
 @pytest.fixture(scope="module", params=list(CASES), ids=list(CASES))
 def big(request):
     name, s, heads = CASES[request.param]
-    wl = inputs.WORKLOADS[name]
+    wl = inputs.WORKLOADS.get(name) or LIMIT_WORKLOADS[name]
     extra = dict(EXTRA.get(request.param, {}))
     import dataclasses
     for field in ("text_tokens", "block", "head_dim"):
@@ -185,3 +194,37 @@ def test_constant_values_give_constant_output(big):
     torch.cuda.synchronize()
     dev = (buf["o"].float() - 1.0).abs().max().item()
     assert dev <= 2 ** -7, dev                      # bf16 rounding of the probabilities and of the output
+
+
+def test_maximum_number_of_heads():
+    """B x Hh = 65,535, the most a plan accepts (the second grid dimension of the permutation and mask
+    launches): five seeded heads repeated 13,107 times.  The five are checked against the oracle; every
+    repetition must equal the first one bit for bit (same inputs, deterministic kernels)."""
+    base = inputs.Workload("limit_heads", 8, 1, 5, 64, 8, 8, 8, 64, 0.5, 1, 0.3)
+    reps = 13107
+    wl = inputs.Workload("limit_heads", 8, 1, base.heads * reps, 64, 8, 8, 8, 64, 0.5, 1, 0.3)
+    assert wl.heads == 65535
+    q5, k5, v5 = inputs.make_qkv(base)
+    plan = hp.make_plan(wl)
+    dev = [x.to(DEV).repeat(1, reps, 1, 1) for x in (q5, k5, v5)]
+    buf = plan.alloc(DEV)
+    o = plan.layer_fused(*dev, buf)
+    torch.cuda.synchronize()
+    i = plan.info
+    for name in ("o", "blk_idx", "blk_cnt", "qbar", "kbar"):
+        t = buf[name][0]
+        first = t[:base.heads]
+        assert torch.equal(t.reshape(reps, *first.shape), first.expand(reps, *first.shape)), name
+    for h in range(base.heads):
+        Q, K, V = (hp.f64(x[0, h]) for x in (q5, k5, v5))
+        r = orc.layer(Q, K, V, T=wl.T, H=wl.H, W=wl.W, block=wl.block, sparsity=wl.sparsity,
+                      sink_frames=wl.sink_frames, window=(i.wt, i.wh, i.ww))
+        for hh in (h, wl.heads - base.heads + h):           # first and last repetition
+            M = hp.gpu_lists_to_mask(buf["blk_idx"][0, hh], buf["blk_cnt"][0, hh], i.n_blocks)
+            firm = r["gap"] > hp.TIE_GAP
+            assert np.array_equal(M[firm], r["M"][firm]), hh
+            want = r["O"] if np.array_equal(M, r["M"]) else orc.unpermute(
+                orc.block_sparse_attention(r["Qp"], r["Kp"], r["Vp"], M, wl.block), r["perm"])
+            err = np.abs(hp.f64(o[0, hh].cpu()) - want)
+            assert err.max() <= hp.ATTN_MAX_ABS and err.mean() <= hp.ATTN_MEAN_ABS, (hh, err.max(), err.mean())
+    plan.close()
