@@ -137,7 +137,8 @@ template <int D, int BQ, int BK>
 __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_kernel(
     const __bf16* __restrict__ qp, const __bf16* __restrict__ kp, const __bf16* __restrict__ vp,
     const int32_t* __restrict__ blk_idx, const int32_t* __restrict__ blk_cnt, __bf16* __restrict__ op,
-    float* __restrict__ lse, const int32_t* __restrict__ row_order, int sink_per_xcd, int plain_per_xcd, int n_bh,
+    float* __restrict__ lse, const int32_t* __restrict__ row_order, int plain_per_xcd, int n_bh, int sink_row_begin,
+    int n_sink_rows, int sink_slots,
     int Tq, int Tb, int k_row, int last_valid, float scale_log2, const int32_t* __restrict__ scatter, int n_tokens,
     int heads, rf2_strides st) {
   // Tq: Q blocks per head (rows of the block mask); Tb: K/V blocks per head (its columns); last_valid:
@@ -153,20 +154,25 @@ __global__ void __launch_bounds__(BQ * 2, BQ >= 128 ? 2 : 1) block_sparse_attn_k
   // jobs first) none of them is left running alone at the end, and the short rows fill the tail evenly.
   // (workgroups with equal blockIdx % 8 share an XCD; which of the eight it is varies from launch to launch)
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  int bh, entry;
-  if (slot < n_bh * sink_per_xcd) {
-    bh = slot / sink_per_xcd;
-    entry = slot % sink_per_xcd;
+  int bh, qi;
+  if (slot < sink_slots) {
+    // The sink rows of all heads, numbered head by head, are cut into 8 contiguous runs of sink_slots
+    // rows, one per XCD: an XCD gets whole heads where it can (with 40 heads of 29 sink rows: five heads
+    // each).  Rows of one head have the same list (every column) and the same length: side by side on
+    // one XCD they run in step and find each other's tiles in its L2.
+    const int g = xcd * sink_slots + slot;
+    if (g >= n_bh * n_sink_rows) return;
+    bh = g / n_sink_rows;
+    qi = sink_row_begin + g % n_sink_rows;
   } else {
-    const int t = slot - n_bh * sink_per_xcd;
+    // The work table deals a head's ordinary rows to 8 shares of slightly different size (contiguous
+    // ranges); the share an XCD takes rotates with the head so that no XCD collects the large shares of
+    // every head.
+    const int t = slot - sink_slots;
     bh = t / plain_per_xcd;
-    entry = sink_per_xcd + t % plain_per_xcd;
+    qi = row_order[((xcd + bh) & 7) * plain_per_xcd + t % plain_per_xcd];
+    if (qi < 0) return;
   }
-  // The work table deals a head's rows to 8 shares of slightly different size (e.g. 29 sink rows:
-  // five shares of 4, three of 3); the share an XCD takes rotates with the head so that no XCD
-  // collects the large shares of every head.
-  const int qi = row_order[((xcd + bh) & 7) * (sink_per_xcd + plain_per_xcd) + entry];
-  if (qi < 0) return;
   const size_t row_id = (size_t)bh * Tq + qi;
   int cnt = blk_cnt[row_id];
   const bool dense = (cnt == Tb);
@@ -490,10 +496,14 @@ int launch_attn(const rf2_plan* plan, const void* qp, const void* kp, const void
   const rf2_info& in = plan->info;
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
   const int n_bh = c.batch * c.heads;
-  const unsigned grid = 8u * (unsigned)(plan->sink_per_xcd + plan->plain_per_xcd) * (unsigned)n_bh;
+  // slots of an XCD: its run of the sink rows of all heads, then plain_per_xcd ordinary rows of every head
+  const int n_sink_rows = in.sink_block_end - in.sink_block_begin;
+  const int sink_slots = (int)(((int64_t)n_bh * n_sink_rows + 7) / 8);
+  const unsigned grid = 8u * ((unsigned)sink_slots + (unsigned)n_bh * (unsigned)plan->plain_per_xcd);
+  if (grid == 0) return RF2_OK;
   block_sparse_attn_kernel<D, BQ, BK><<<dim3(grid), dim3(C::NT), 0, st>>>(
       (const __bf16*)qp, (const __bf16*)kp, (const __bf16*)vp, blk_idx, blk_cnt, (__bf16*)op, lse, plan->d_row_order,
-      plan->sink_per_xcd, plan->plain_per_xcd, n_bh, in.n_blocks, in.n_blocks_k, in.k_row, in.last_block_valid_k,
+      plan->plain_per_xcd, n_bh, in.sink_block_begin, n_sink_rows, sink_slots, in.n_blocks, in.n_blocks_k, in.k_row, in.last_block_valid_k,
       scale_log2, scatter ? plan->d_perm : nullptr, (int)in.N, c.heads, rf2_qkv_strides(plan));
   RF2_LAUNCH_CHECK();
   return RF2_OK;

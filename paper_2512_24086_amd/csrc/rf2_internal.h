@@ -14,8 +14,8 @@ struct rf2_plan {
   std::vector<int32_t> perm, inv;  // host copies, N entries each
   int32_t* d_perm;                 // device, N_pad entries; -1 marks a padding row
   int32_t* d_inv;                  // device, N entries
-  int32_t* d_row_order;            // device, [8][sink_per_xcd + plain_per_xcd]: Q block of each workgroup slot, -1 = none
-  int32_t sink_per_xcd, plain_per_xcd;
+  int32_t* d_row_order;            // device, [8][plain_per_xcd]: ordinary Q block of each workgroup slot of a head, -1 = none
+  int32_t plain_per_xcd;
 };
 
 // Strides (in rows of d elements) of the caller's q, k, v, o tensors: row of token n of head h of

@@ -179,27 +179,23 @@ int rf2_plan_create(const rf2_config* cfg, rf2_plan** out) {
       }
   for (int64_t n = n_video; n < N; ++n) p->inv[(size_t)n] = p->perm[(size_t)n] = (int32_t)n;   // text: in place, last
 
-  // Work tables of the attention kernel.  Workgroups g with equal g % 8 run on one XCD.  A head's all-column
-  // sink rows are dealt round-robin to the XCDs; each XCD also gets a contiguous range of the
-  // head's ordinary Q blocks (neighbouring blocks tend to pick the same K blocks, so they share
-  // its L2).  The kernel decides the issue order of the two kinds (sink rows run ahead).
-  const int sb = in.sink_block_begin, se = in.sink_block_end;
-  std::vector<std::vector<int32_t>> sink_xcd(8), plain_xcd(8);
-  for (int i = sb; i < se; ++i) sink_xcd[(i - sb) % 8].push_back(i);
+  // Work table of the attention kernel.  Workgroups g with equal g % 8 run on one XCD.  Each XCD gets a
+  // contiguous range of a head's ordinary Q blocks (neighbouring blocks tend to pick the same K blocks, so
+  // they share its L2).  The all-column sink rows need no table: the kernel deals them out itself, in
+  // contiguous runs over all heads, and issues them ahead of the ordinary rows.
+  const int sb = in.sink_block_begin;
+  std::vector<std::vector<int32_t>> plain_xcd(8);
   const int n_plain = Tb - nS;
   for (int r = 0; r < n_plain; ++r) {
     const int i = r < sb ? r : r + nS;
     plain_xcd[(int)(((int64_t)r * 8) / std::max(n_plain, 1))].push_back(i);
   }
-  size_t spx = 0, ppx = 0;
-  for (int x = 0; x < 8; ++x) { spx = std::max(spx, sink_xcd[x].size()); ppx = std::max(ppx, plain_xcd[x].size()); }
-  p->sink_per_xcd = (int32_t)spx;
+  size_t ppx = 0;
+  for (int x = 0; x < 8; ++x) ppx = std::max(ppx, plain_xcd[x].size());
   p->plain_per_xcd = (int32_t)ppx;
-  std::vector<int32_t> order(8 * (spx + ppx), -1);      // [xcd][sink slots | plain slots], -1 = no work
-  for (int x = 0; x < 8; ++x) {
-    for (size_t r = 0; r < sink_xcd[x].size(); ++r) order[x * (spx + ppx) + r] = sink_xcd[x][r];
-    for (size_t r = 0; r < plain_xcd[x].size(); ++r) order[x * (spx + ppx) + spx + r] = plain_xcd[x][r];
-  }
+  std::vector<int32_t> order(std::max<size_t>(8 * ppx, 1), -1);      // [share][slot], -1 = no work
+  for (int x = 0; x < 8; ++x)
+    for (size_t r = 0; r < plain_xcd[x].size(); ++r) order[x * ppx + r] = plain_xcd[x][r];
 
   std::vector<int32_t> perm_pad((size_t)std::max(in.N_pad, in.N_pad_k), -1);
   std::memcpy(perm_pad.data(), p->perm.data(), (size_t)N * sizeof(int32_t));
