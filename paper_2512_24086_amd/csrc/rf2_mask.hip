@@ -60,18 +60,28 @@ __global__ void __launch_bounds__(256) predict_mask_kernel(
     for (int kk = 0; kk < D / 16; ++kk) a[kk] = *reinterpret_cast<const f32x4*>(qb + (size_t)row * D + 16 * kk + 4 * lk);
   }
   const int n_ct = (Tb + 15) / 16;
-  for (int ct = wave; ct < n_ct; ct += 4) {
+  // the operand rows of the next column tile are requested before the products of the current one are
+  // issued (a wavefront has ~10 tiles; unpipelined, each tile waits out a full trip to L2)
+  auto load_tile = [&](f32x4 (&b)[D / 16], int ct) {
     const int col = min(ct * 16 + lr, Tb - 1);
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) b[kk] = *reinterpret_cast<const f32x4*>(kb + (size_t)col * D + 16 * kk + 4 * lk);
+  };
+  f32x4 bcur[D / 16], bnext[D / 16];
+  if (wave < n_ct) load_tile(bcur, wave);
+  for (int ct = wave; ct < n_ct; ct += 4) {
+    if (ct + 4 < n_ct) load_tile(bnext, ct + 4);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk) {
-      const f32x4 b = *reinterpret_cast<const f32x4*>(kb + (size_t)col * D + 16 * kk + 4 * lk);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[kk][e], b[e], acc, 0, 0, 0);
+      for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[kk][e], bcur[kk][e], acc, 0, 0, 0);
     }
     // acc[i] = S_hat[i0 + 4*lk + i][ct*16 + lr]
 #pragma unroll
     for (int i = 0; i < 4; ++i) sc[(4 * lk + i) * LD + ct * 16 + lr] = acc[i];
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) bcur[kk] = bnext[kk];
   }
   __syncthreads();
 
@@ -113,14 +123,17 @@ __global__ void __launch_bounds__(256) predict_mask_kernel(
           int cnt = 0;
 #pragma unroll
           for (int e = 0; e < EMAX; ++e)
-            if (e < E) cnt += popc64(__builtin_amdgcn_ballot_w64(key[e] >= cand));
+            cnt += popc64(__builtin_amdgcn_ballot_w64(key[e] >= cand));   // (keys past the row are 0 < cand)
           if (cnt >= k_sel) T = cand;
+          // exactly k_sel keys at or above T: lower bits can only raise T towards the smallest of them
+          // without changing that set, and the tie rule below sees the same set either way
+          if (cnt == k_sel) break;
         }
       }
       int greater = 0;
 #pragma unroll
       for (int e = 0; e < EMAX; ++e)
-        if (e < E) greater += popc64(__builtin_amdgcn_ballot_w64(key[e] > T));
+        greater += popc64(__builtin_amdgcn_ballot_w64(key[e] > T));
       need_eq = k_sel - greater;
     } else {
       // Softmax mass of every candidate (relative to the row maximum, unnormalised), then the
@@ -183,9 +196,15 @@ struct MaskLaunch {
   size_t lds;
 };
 
+// The kernel is instantiated for a few row widths (EMAX keys per lane): the search loops run over
+// EMAX keys without bounds checks (keys past the row are 0), so a snug width saves compares.
 template <int D>
 const void* mask_kernel_for(int E, bool cdf) {
+  if (E <= 8) return cdf ? (const void*)predict_mask_kernel<D, 8, true> : (const void*)predict_mask_kernel<D, 8, false>;
+  if (E <= 12) return cdf ? (const void*)predict_mask_kernel<D, 12, true> : (const void*)predict_mask_kernel<D, 12, false>;
   if (E <= 16) return cdf ? (const void*)predict_mask_kernel<D, 16, true> : (const void*)predict_mask_kernel<D, 16, false>;
+  if (E <= 20) return cdf ? (const void*)predict_mask_kernel<D, 20, true> : (const void*)predict_mask_kernel<D, 20, false>;
+  if (E <= 24) return cdf ? (const void*)predict_mask_kernel<D, 24, true> : (const void*)predict_mask_kernel<D, 24, false>;
   return cdf ? (const void*)predict_mask_kernel<D, 32, true> : (const void*)predict_mask_kernel<D, 32, false>;
 }
 
